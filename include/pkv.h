@@ -1,0 +1,183 @@
+/*
+ * pkv.h -- C ABI of libpkv: PyramidKV prefill-time KV-cache compression
+ * (arXiv 2406.02069) for AMD MI355X (gfx950).
+ *
+ * For every transformer layer l the library keeps k^l of the n cached tokens
+ * of each KV head: the last alpha "instruction" tokens, plus the k^l - alpha
+ * prefix tokens that receive the most softmax attention from the instruction
+ * queries (Sec. 4.2.2).  The per-layer budgets k^l follow the paper's
+ * arithmetic "pyramid" (Sec. 4.2.1).  The kept K/V rows are copied, in
+ * ascending position order, into a new smaller cache (appendix "Details of
+ * Proposed Method": eviction by gather; appendix on rotary embeddings: kept
+ * rows are not re-rotated and positions stay ascending).
+ *
+ * Conventions
+ *  - Plain C, no C++/torch types.  Every function returns a pkv_status
+ *    (0 = ok) except the pure size/string helpers.
+ *  - Pointers marked DEVICE must be device memory owned by the caller and
+ *    stay valid until the work queued on `stream` has finished.  Pointers
+ *    marked HOST are read/written synchronously during the call.
+ *  - Argument errors are detected on the host before anything is launched
+ *    and leave all outputs untouched.
+ *  - Launching calls are asynchronous on `stream` (a hipStream_t passed as
+ *    void*; NULL = the default stream).  They never synchronise and never
+ *    allocate or free memory.  Results are deterministic: the same inputs
+ *    give bit-identical outputs.
+ *  - Inputs are never modified.
+ */
+#ifndef PKV_H_
+#define PKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PKV_OK = 0,
+  PKV_ERR_INVALID_ARG = 1, /* NULL pointer, bad size, bad stride, bad enum   */
+  PKV_ERR_UNSUPPORTED = 2, /* valid in the paper's terms, not built here     */
+  PKV_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned or too small        */
+  PKV_ERR_HIP = 4          /* a kernel launch was rejected by the runtime    */
+} pkv_status;
+
+typedef enum {
+  PKV_POOL_NONE = 0,
+  PKV_POOL_MAX = 1,
+  PKV_POOL_AVG = 2
+} pkv_pool;
+
+/*
+ * Per-layer budgets (Sec. 4.2.1, Eq. budget).  HOST only, pure.
+ *
+ * The alpha instruction tokens are kept in every layer; the pyramid is laid
+ * over the remaining A = avg_budget - alpha entries per layer
+ * (k_total = L*A): top layer A/beta, bottom layer 2A - A/beta, arithmetic
+ * sequence in between.  The real-valued sequence is made integer by flooring
+ * and handing the missing units to the layers with the largest fractional
+ * parts (ties to the lower layer), so that
+ *     sum_l k_out[l] == L * avg_budget   and   k_out[l] >= k_out[l+1].
+ * k_out[l] INCLUDES the alpha instruction tokens.  L == 1 gives avg_budget;
+ * beta == 1 gives a uniform budget.
+ *
+ * k_out: HOST, int32[L], written.
+ * Errors: L < 1, beta < 1, alpha < 0, avg_budget < alpha, k_out NULL
+ *         -> PKV_ERR_INVALID_ARG.
+ */
+int pkv_budgets(int32_t L, int32_t avg_budget, int32_t beta, int32_t alpha,
+                int32_t* k_out);
+
+/*
+ * Shape of one layer's compression problem.  Strides are in ELEMENTS (bf16);
+ * the head dimension is always contiguous.
+ */
+typedef struct {
+  int32_t B;      /* sequences in the batch, >= 1                            */
+  int32_t Hq;     /* query heads; Hq % Hkv == 0                              */
+  int32_t Hkv;    /* key/value heads                                         */
+  int32_t d;      /* head dimension d_k: 64 or 128                           */
+  int32_t N;      /* (padded) cached length of K and V, >= 1                 */
+  int32_t alpha;  /* instruction-token window, 1 <= alpha <= 64              */
+  int32_t k_l;    /* this layer's budget including the window, >= alpha      */
+  int32_t pool;   /* pkv_pool                                                */
+  int32_t pool_w; /* pooling width, odd, 1..63 (1 == no pooling)             */
+  int32_t reserved; /* must be 0                                             */
+  int64_t q_sb, q_sh, q_st;    /* strides of Q_win [B, Hq, alpha, d]         */
+  int64_t kv_sb, kv_sh, kv_st; /* strides of K and of V [B, Hkv, N, d]       */
+  int64_t o_sb, o_sh, o_st;    /* strides of K_out and V_out
+                                  [B, Hkv, k_cap, d], k_cap = min(k_l, N)    */
+} pkv_layer_desc;
+
+/*
+ * Bytes of DEVICE workspace pkv_compress_layer needs for this shape (also
+ * enough for pkv_compress_layers over layers of this shape with any k_l).
+ * HOST only, pure.  Returns 0 if the descriptor is invalid.
+ */
+size_t pkv_workspace_bytes(const pkv_layer_desc* desc);
+
+/*
+ * Compress one layer (Sec. 4.2.2; gather per the appendix "Details of
+ * Proposed Method").
+ *
+ * For each sequence b with n = seq_lens[b] valid tokens and each KV head g
+ * (G = Hq/Hkv query heads h = g*G .. g*G+G-1 share it):
+ *   1. if k_l >= n every token is kept;
+ *   2. otherwise each window query t (absolute position n-alpha+t) attends
+ *      causally: A = softmax over keys 0..n-alpha+t of q.k / sqrt(d)
+ *      (Eq. Al), window keys included;
+ *   3. s^h_i = sum_t A^{(h,t)}_i for prefix keys i < n-alpha (Eq. att_score),
+ *      averaged over the G heads of the group;
+ *   4. the scores are pooled along the sequence (stride 1, same length; max
+ *      ignores out-of-range neighbours, avg counts them as zero and divides
+ *      by pool_w);
+ *   5. the k_l-alpha prefix positions with the largest pooled score are
+ *      kept (equal scores: the lower position wins), in ascending order,
+ *      followed by the window positions n-alpha .. n-1;
+ *   6. K_out/V_out rows are bit copies of the kept K/V rows.
+ * Arithmetic: bf16 inputs, fp32 accumulation and scores.
+ *
+ * desc       HOST.
+ * Q_win      DEVICE bf16 [B,Hq,alpha,d]: queries of the LAST alpha valid
+ *            tokens of each sequence (positions n_b-alpha .. n_b-1), as used
+ *            by attention (after any rotary embedding).
+ * K, V       DEVICE bf16 [B,Hkv,N,d], same strides.  Rows >= n_b are never
+ *            read.  V is read only at the kept rows.
+ * seq_lens   DEVICE int32[B] with 0 <= n_b <= N, or NULL (all n_b == N).
+ *            Values outside the range are clamped on the device.
+ *            If n_b <= k_l all n_b tokens are kept (this covers n_b < alpha).
+ * K_out,V_out DEVICE bf16 [B,Hkv,k_cap,d], written.  Rows >= count are zero.
+ * idx_out    DEVICE int32 [B,Hkv,k_cap] contiguous, written: kept positions,
+ *            ascending; the last min(alpha,n_b) valid entries are the window;
+ *            entries >= count are -1.
+ * count_out  DEVICE int32 [B], written: min(k_l, n_b).
+ * scores_out DEVICE fp32 [B,Hkv,N] contiguous, or NULL: pooled scores before
+ *            selection, defined for i < n_b-alpha when k_l < n_b; other
+ *            entries are left untouched.
+ * workspace  DEVICE, 256-byte aligned, >= pkv_workspace_bytes(desc) bytes;
+ *            contents on entry are irrelevant, contents on exit undefined.
+ *            Concurrent calls must use distinct workspaces.
+ * stream     hipStream_t.
+ *
+ * Errors: PKV_ERR_INVALID_ARG (NULL required pointer, shape/stride rules
+ * above violated, reserved != 0), PKV_ERR_UNSUPPORTED (d not 64/128,
+ * alpha > 64, pool_w > 63), PKV_ERR_WORKSPACE, PKV_ERR_HIP.
+ */
+int pkv_compress_layer(const pkv_layer_desc* desc, const void* Q_win,
+                       const void* K, const void* V, const int32_t* seq_lens,
+                       void* K_out, void* V_out, int32_t* idx_out,
+                       int32_t* count_out, float* scores_out, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/*
+ * Compress L layers of one request batch (the whole prefill-time step: every
+ * layer has its own Q_win/K/V and its own budget descs[l].k_l, Sec. 4.2.1).
+ * Same results as L calls of pkv_compress_layer, queued so that independent
+ * stages of neighbouring layers can overlap on the device.
+ *
+ * descs      HOST, L descriptors.  All fields except k_l and the output
+ *            strides must be equal across layers.
+ * Q_win, K, V, K_out, V_out, idx_out, count_out, scores_out
+ *            HOST arrays of L DEVICE pointers, each as in
+ *            pkv_compress_layer (scores_out may be NULL, or hold NULLs).
+ * seq_lens   DEVICE int32[B] or NULL; shared by all layers.
+ * workspace  DEVICE, >= pkv_workspace_bytes(&descs[0]) bytes.
+ * Errors: as pkv_compress_layer; additionally L < 1 or differing layer
+ * shapes -> PKV_ERR_INVALID_ARG.
+ */
+int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs,
+                        const void* const* Q_win, const void* const* K,
+                        const void* const* V, const int32_t* seq_lens,
+                        void* const* K_out, void* const* V_out,
+                        int32_t* const* idx_out, int32_t* const* count_out,
+                        float* const* scores_out, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/* Static, NUL-terminated description of a pkv_status value.  HOST only. */
+const char* pkv_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PKV_H_ */

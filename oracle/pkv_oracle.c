@@ -1,0 +1,320 @@
+/*
+ * pkv_oracle.c -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, step-by-step CPU statement of PyramidKV's prefill-time
+ * KV-cache compression (arXiv 2406.02069), written to be checked against the
+ * paper by eye.  It is the reference the GPU library is compared with; it is
+ * never part of the product path, shares no code with the HIP library and is
+ * never tuned.  All floating point is fp64 on the exact values of the bf16
+ * inputs.  The only parallelism is OpenMP over independent query rows and
+ * independent (sequence, KV head) units; nothing is blocked, fused or
+ * reordered.
+ *
+ * Pins (tests/test_oracle_*.py): library softmax for the alpha=1 special
+ * case, the harmonic closed form for identical keys (causal mask, window sum,
+ * group mean), library 1-D pooling, brute-force sorting on tiny inputs,
+ * planted one-hot / sink patterns, window retention, full-cache edge and the
+ * closed forms of the budget sequence.  The integer rounding of the budgets,
+ * the pool padding rule and the GQA mean are conventions the paper does not
+ * fix ("parity unpinned" by the paper; pinned only to the stated reading).
+ *
+ * Notation follows the paper: m layers (here L), n tokens, d = d_k, alpha
+ * instruction tokens, beta pyramid shape, k^l budget of layer l.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define PKVO_POOL_NONE 0
+#define PKVO_POOL_MAX 1
+#define PKVO_POOL_AVG 2
+
+/* bf16 -> double, exact: a bf16 is the upper half of an IEEE fp32. */
+static double bf16_to_f64(uint16_t h) {
+  uint32_t u = ((uint32_t)h) << 16;
+  float f;
+  memcpy(&f, &u, sizeof f);
+  return (double)f;
+}
+
+/* ------------------------------------------------------------------------
+ * Budget allocation (Sec. 4.2.1, Eq. budget).
+ *
+ * The alpha instruction tokens are retained in every layer; the pyramid is
+ * laid over the REMAINING budget A = avg - alpha per layer, k_total = L*A:
+ *   top    k^{m-1} = k_total / (beta*m)           = A / beta
+ *   bottom k^0     = 2*k_total/m - k^{m-1}        = 2A - A/beta
+ *   k^l = k^0 - (k^0 - k^{m-1})/(m-1) * l         (arithmetic sequence)
+ * which is r_l = A*[(2beta-1)(L-1) - 2(beta-1) l] / (beta (L-1)).
+ * Integerisation (not fixed by the paper): floor every r_l, then hand the
+ * missing units, one each, to the layers with the largest fractional part,
+ * ties to the lower layer.  k_out[l] = alpha + that integer.
+ * Returns 0, or 1 for invalid arguments.
+ * ---------------------------------------------------------------------- */
+int pkvo_budgets(int32_t L, int32_t avg, int32_t beta, int32_t alpha,
+                 int32_t *k_out) {
+  if (L < 1 || beta < 1 || alpha < 0 || avg < alpha || !k_out) return 1;
+  int64_t A = (int64_t)avg - alpha;
+  if (L == 1) {
+    k_out[0] = avg;
+    return 0;
+  }
+  int64_t den = (int64_t)beta * (L - 1);
+  int64_t *rem = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
+  int64_t sum_floor = 0;
+  for (int32_t l = 0; l < L; ++l) {
+    int64_t num = A * ((2 * (int64_t)beta - 1) * (L - 1) -
+                       2 * ((int64_t)beta - 1) * l);
+    int64_t f = num / den; /* num >= 0 */
+    rem[l] = num % den;
+    k_out[l] = (int32_t)f;
+    sum_floor += f;
+  }
+  int64_t left = (int64_t)L * A - sum_floor;
+  while (left > 0) {
+    int32_t best = -1;
+    for (int32_t l = 0; l < L; ++l)
+      if (rem[l] >= 0 && (best < 0 || rem[l] > rem[best])) best = l;
+    k_out[best] += 1;
+    rem[best] = -1; /* each layer gets at most one extra unit */
+    --left;
+  }
+  for (int32_t l = 0; l < L; ++l) k_out[l] += alpha;
+  free(rem);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Window attention received by every prefix key (Sec. 4.2.2, Eq. Al and
+ * Eq. att_score), for one sequence of n tokens and one KV head g whose
+ * group holds G query heads.
+ *
+ *   q  : [G][alpha][d]  queries of the last alpha tokens (positions
+ *                       n-alpha .. n-1) of the G heads of the group
+ *   k  : [n][d]         keys of the KV head
+ *   s_head : [G][n-alpha] out, s^h_i = sum_t A^{(h,t)}_i   (may be NULL)
+ *   s_mean : [n-alpha]    out, (1/G) sum_h s^h_i
+ *
+ * Each window query at absolute position p attends causally to keys 0..p;
+ * its softmax runs over exactly those p+1 keys (window keys included).
+ * Scores are reported for prefix keys i < n-alpha only.
+ * ---------------------------------------------------------------------- */
+static void window_scores_unit(int32_t G, int32_t alpha, int32_t d, int32_t n,
+                               const uint16_t *q, const uint16_t *k,
+                               double *s_head, double *s_mean) {
+  const int32_t npre = n - alpha;
+  const int32_t R = G * alpha;
+  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  /* A[r][i]: attention of query row r = h*alpha + t on key i (0 beyond p). */
+  double *A = (double *)malloc(sizeof(double) * (size_t)R * (size_t)n);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t r = 0; r < R; ++r) {
+    const int32_t t = r % alpha;
+    const int32_t p = npre + t; /* absolute position of this query */
+    double *Ar = A + (size_t)r * n;
+    const uint16_t *qr = q + (size_t)r * d;
+    double mx = -INFINITY;
+    for (int32_t i = 0; i <= p; ++i) {
+      double dot = 0.0;
+      for (int32_t c = 0; c < d; ++c)
+        dot += bf16_to_f64(qr[c]) * bf16_to_f64(k[(size_t)i * d + c]);
+      Ar[i] = dot * inv_sqrt_d;
+      if (Ar[i] > mx) mx = Ar[i];
+    }
+    double Z = 0.0;
+    for (int32_t i = 0; i <= p; ++i) {
+      Ar[i] = exp(Ar[i] - mx);
+      Z += Ar[i];
+    }
+    for (int32_t i = 0; i <= p; ++i) Ar[i] /= Z;
+    for (int32_t i = p + 1; i < n; ++i) Ar[i] = 0.0;
+  }
+  for (int32_t i = 0; i < npre; ++i) {
+    double mean = 0.0;
+    for (int32_t h = 0; h < G; ++h) {
+      double sh = 0.0;
+      for (int32_t t = 0; t < alpha; ++t)
+        sh += A[(size_t)(h * alpha + t) * n + i];
+      if (s_head) s_head[(size_t)h * npre + i] = sh;
+      mean += sh;
+    }
+    s_mean[i] = mean / (double)G;
+  }
+  free(A);
+}
+
+/* Exported form of the above for stage-wise tests.  n > alpha >= 1. */
+int pkvo_window_scores(int32_t G, int32_t alpha, int32_t d, int32_t n,
+                       const uint16_t *q, const uint16_t *k, double *s_head,
+                       double *s_mean) {
+  if (G < 1 || alpha < 1 || d < 1 || n <= alpha || !q || !k || !s_mean)
+    return 1;
+  window_scores_unit(G, alpha, d, n, q, k, s_head, s_mean);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * 1-D pooling of the prefix scores along the sequence ("a pooling layer",
+ * Sec. 4.2.2): stride 1, same length, odd width w, half-width r=(w-1)/2.
+ *   max: maximum over the in-range neighbours |u| <= r.
+ *   avg: sum over the in-range neighbours divided by w (out-of-range
+ *        neighbours count as zero).
+ *   none, or w == 1: identity.
+ * ---------------------------------------------------------------------- */
+int pkvo_pool(int32_t pool, int32_t w, int32_t len, const double *s,
+              double *p) {
+  if (w < 1 || (w % 2) == 0 || len < 0) return 1;
+  if (pool != PKVO_POOL_NONE && pool != PKVO_POOL_MAX && pool != PKVO_POOL_AVG)
+    return 1;
+  const int32_t r = (w - 1) / 2;
+  for (int32_t i = 0; i < len; ++i) {
+    if (pool == PKVO_POOL_NONE || w == 1) {
+      p[i] = s[i];
+    } else if (pool == PKVO_POOL_MAX) {
+      double mx = -INFINITY;
+      for (int32_t u = -r; u <= r; ++u)
+        if (i + u >= 0 && i + u < len && s[i + u] > mx) mx = s[i + u];
+      p[i] = mx;
+    } else {
+      double acc = 0.0;
+      for (int32_t u = -r; u <= r; ++u)
+        if (i + u >= 0 && i + u < len) acc += s[i + u];
+      p[i] = acc / (double)w;
+    }
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Top-kk of p[0..len) in the total order (value descending, index
+ * ascending), returned sorted by ascending index (Sec. 4.2.2: "the top k^l
+ * tokens with the highest scores are selected"; lower index wins ties).
+ * ---------------------------------------------------------------------- */
+typedef struct {
+  double v;
+  int32_t i;
+} pkvo_pair;
+
+static int cmp_value_desc_index_asc(const void *a, const void *b) {
+  const pkvo_pair *x = (const pkvo_pair *)a, *y = (const pkvo_pair *)b;
+  if (x->v > y->v) return -1;
+  if (x->v < y->v) return 1;
+  return (x->i > y->i) - (x->i < y->i);
+}
+
+static int cmp_int_asc(const void *a, const void *b) {
+  int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+  return (x > y) - (x < y);
+}
+
+int pkvo_topk(int32_t len, const double *p, int32_t kk, int32_t *idx) {
+  if (kk < 0 || kk > len) return 1;
+  pkvo_pair *a = (pkvo_pair *)malloc(sizeof(pkvo_pair) * (size_t)(len + 1));
+  for (int32_t i = 0; i < len; ++i) {
+    a[i].v = p[i];
+    a[i].i = i;
+  }
+  qsort(a, (size_t)len, sizeof(pkvo_pair), cmp_value_desc_index_asc);
+  for (int32_t j = 0; j < kk; ++j) idx[j] = a[j].i;
+  qsort(idx, (size_t)kk, sizeof(int32_t), cmp_int_asc);
+  free(a);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * One layer of compression for a (possibly ragged) batch.
+ *
+ * Contiguous layouts:
+ *   Q_win [B][Hq][alpha][d]   bf16 bits; queries of the LAST alpha valid
+ *                             tokens of each sequence
+ *   K, V  [B][Hkv][N][d]      bf16 bits; rows >= seq_lens[b] are never read
+ *   seq_lens [B] or NULL (all N)
+ *   k_cap = min(k_l, N)
+ *   K_out, V_out [B][Hkv][k_cap][d]   kept rows, bit copies; rest zero
+ *   idx_out [B][Hkv][k_cap]           kept positions ascending, window
+ *                                     last; rest -1
+ *   count_out [B]                     min(k_l, n_b)
+ *   pooled_out [B][Hkv][N] (optional) pooled scores of prefix keys; entries
+ *                                     at i >= n_b - alpha, and everything
+ *                                     when k_l >= n_b, are set to 0
+ * Steps per sequence b (length n) and KV head g:
+ *   1. k_l >= n: keep everything.
+ *   2-4. window scores, sum over window, mean over group (above).
+ *   5. pool.  6. top-(k_l - alpha) of the prefix, ascending, then the
+ *   window positions n-alpha..n-1.  7. copy the kept K and V rows.
+ * Returns 0, or 1 for invalid arguments.
+ * ---------------------------------------------------------------------- */
+int pkvo_compress_layer(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
+                        int32_t N, int32_t alpha, int32_t k_l, int32_t pool,
+                        int32_t pool_w, const uint16_t *Q_win,
+                        const uint16_t *K, const uint16_t *V,
+                        const int32_t *seq_lens, uint16_t *K_out,
+                        uint16_t *V_out, int32_t *idx_out, int32_t *count_out,
+                        double *pooled_out) {
+  if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv || d < 1 || N < 1 || alpha < 1 ||
+      k_l < alpha || pool_w < 1 || (pool_w % 2) == 0)
+    return 1;
+  if (pool != PKVO_POOL_NONE && pool != PKVO_POOL_MAX && pool != PKVO_POOL_AVG)
+    return 1;
+  const int32_t G = Hq / Hkv;
+  const int32_t k_cap = k_l < N ? k_l : N;
+  for (int32_t b = 0; b < B; ++b) {
+    if (seq_lens && (seq_lens[b] < 0 || seq_lens[b] > N)) return 1;
+  }
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t n = seq_lens ? seq_lens[b] : N;
+    const int32_t count = k_l < n ? k_l : n;
+    count_out[b] = count;
+    for (int32_t g = 0; g < Hkv; ++g) {
+      const size_t unit = (size_t)b * Hkv + g;
+      const uint16_t *Kg = K + unit * (size_t)N * d;
+      const uint16_t *Vg = V + unit * (size_t)N * d;
+      int32_t *idx = idx_out + unit * (size_t)k_cap;
+      uint16_t *Ko = K_out + unit * (size_t)k_cap * d;
+      uint16_t *Vo = V_out + unit * (size_t)k_cap * d;
+      double *po = pooled_out ? pooled_out + unit * (size_t)N : NULL;
+      if (po)
+        for (int32_t i = 0; i < N; ++i) po[i] = 0.0;
+      if (k_l >= n) {
+        for (int32_t j = 0; j < n; ++j) idx[j] = j;
+      } else {
+        const int32_t npre = n - alpha;
+        const uint16_t *qg =
+            Q_win + ((size_t)b * Hq + (size_t)g * G) * (size_t)alpha * d;
+        double *s = (double *)malloc(sizeof(double) * (size_t)npre);
+        double *p = (double *)malloc(sizeof(double) * (size_t)npre);
+        window_scores_unit(G, alpha, d, n, qg, Kg, NULL, s);
+        pkvo_pool(pool, pool_w, npre, s, p);
+        pkvo_topk(npre, p, k_l - alpha, idx);
+        for (int32_t t = 0; t < alpha; ++t) idx[k_l - alpha + t] = npre + t;
+        if (po) memcpy(po, p, sizeof(double) * (size_t)npre);
+        free(s);
+        free(p);
+      }
+      for (int32_t j = 0; j < k_cap; ++j) {
+        if (j < count) {
+          memcpy(Ko + (size_t)j * d, Kg + (size_t)idx[j] * d,
+                 sizeof(uint16_t) * (size_t)d);
+          memcpy(Vo + (size_t)j * d, Vg + (size_t)idx[j] * d,
+                 sizeof(uint16_t) * (size_t)d);
+        } else {
+          idx[j] = -1;
+          memset(Ko + (size_t)j * d, 0, sizeof(uint16_t) * (size_t)d);
+          memset(Vo + (size_t)j * d, 0, sizeof(uint16_t) * (size_t)d);
+        }
+      }
+    }
+  }
+  return 0;
+}
+
+/* Number of OpenMP threads the scoring loop will use (for reports). */
+int pkvo_num_threads(void) {
+#ifdef _OPENMP
+  extern int omp_get_max_threads(void);
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

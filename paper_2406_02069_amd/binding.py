@@ -1,0 +1,184 @@
+"""Thin Python binding of the C-ABI library libpkv (include/pkv.h).
+
+Argument marshalling only: torch tensors supply device memory and the current
+stream; every step of the method runs in the library's HIP kernels.  There is
+no CPU fallback: if libpkv.so is missing or a call fails, an exception is raised.
+Function names mirror the C entry points.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpkv.so")
+
+POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
+
+EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers", "pkv_status_string"]
+
+
+class PkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("B", "Hq", "Hkv", "d", "N", "alpha", "k_l", "pool", "pool_w", "reserved")] + \
+               [(n, ctypes.c_int64) for n in
+                ("q_sb", "q_sh", "q_st", "kv_sb", "kv_sh", "kv_st", "o_sb", "o_sh", "o_st")]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libpkv.so (built in-tree by paper_2406_02069_amd.build).  Fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2406_02069_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        lib.pkv_budgets.argtypes = [i32, i32, i32, i32, vp]
+        lib.pkv_budgets.restype = ctypes.c_int
+        lib.pkv_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc)]
+        lib.pkv_workspace_bytes.restype = ctypes.c_size_t
+        lib.pkv_compress_layer.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 10 + [ctypes.c_size_t, vp]
+        lib.pkv_compress_layer.restype = ctypes.c_int
+        lib.pkv_compress_layers.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 10 + [ctypes.c_size_t, vp]
+        lib.pkv_compress_layers.restype = ctypes.c_int
+        lib.pkv_status_string.argtypes = [ctypes.c_int]
+        lib.pkv_status_string.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().pkv_status_string(int(status)).decode()
+
+
+def budgets(L: int, avg_budget: int, beta: int, alpha: int) -> List[int]:
+    """pkv_budgets: per-layer cache sizes k_l (window included)."""
+    out = (ctypes.c_int32 * max(L, 1))()
+    rc = load().pkv_budgets(L, avg_budget, beta, alpha, ctypes.cast(out, ctypes.c_void_p))
+    if rc != OK:
+        raise PkvError(rc, "pkv_budgets")
+    return [int(x) for x in out[:L]]
+
+
+def _check_bf16(t: torch.Tensor, name: str):
+    if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError(f"{name}: need a 4-d bf16 tensor with a contiguous last dimension")
+
+
+def make_desc(Q_win: torch.Tensor, K: torch.Tensor, k_l: int, pool: int, pool_w: int,
+              K_out: Optional[torch.Tensor] = None) -> LayerDesc:
+    B, Hq, alpha, d = Q_win.shape
+    _, Hkv, N, _ = K.shape
+    k_cap = min(int(k_l), N)
+    if K_out is not None:
+        o = (K_out.stride(0), K_out.stride(1), K_out.stride(2))
+    else:
+        o = (Hkv * k_cap * d, k_cap * d, d)
+    return LayerDesc(B, Hq, Hkv, d, N, alpha, int(k_l), int(pool), int(pool_w), 0,
+                     Q_win.stride(0), Q_win.stride(1), Q_win.stride(2),
+                     K.stride(0), K.stride(1), K.stride(2), o[0], o[1], o[2])
+
+
+def workspace_bytes(desc: LayerDesc) -> int:
+    return int(load().pkv_workspace_bytes(ctypes.byref(desc)))
+
+
+def alloc_workspace(desc: LayerDesc, device) -> torch.Tensor:
+    nbytes = workspace_bytes(desc)
+    if nbytes == 0:
+        raise PkvError(ERR_INVALID_ARG, "pkv_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)  # torch allocations are >= 256-byte aligned
+
+
+def alloc_outputs(Q_win: torch.Tensor, K: torch.Tensor, k_l: int, want_scores: bool = False):
+    B, Hq, alpha, d = Q_win.shape
+    _, Hkv, N, _ = K.shape
+    k_cap = min(int(k_l), N)
+    dev = K.device
+    K_out = torch.empty((B, Hkv, k_cap, d), dtype=torch.bfloat16, device=dev)
+    V_out = torch.empty((B, Hkv, k_cap, d), dtype=torch.bfloat16, device=dev)
+    idx = torch.empty((B, Hkv, k_cap), dtype=torch.int32, device=dev)
+    count = torch.empty((B,), dtype=torch.int32, device=dev)
+    scores = torch.zeros((B, Hkv, N), dtype=torch.float32, device=dev) if want_scores else None
+    return K_out, V_out, idx, count, scores
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(device) -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def compress_layer(Q_win: torch.Tensor, K: torch.Tensor, V: torch.Tensor, k_l: int, pool: int, pool_w: int,
+                   seq_lens: Optional[torch.Tensor] = None, outputs=None, workspace: Optional[torch.Tensor] = None,
+                   want_scores: bool = False):
+    """pkv_compress_layer on the current torch stream.  Returns (K_out, V_out, idx, count, scores)."""
+    _check_bf16(Q_win, "Q_win"), _check_bf16(K, "K"), _check_bf16(V, "V")
+    if V.shape != K.shape or V.stride() != K.stride():
+        raise ValueError("K and V must have the same shape and strides")
+    if outputs is None:
+        outputs = alloc_outputs(Q_win, K, k_l, want_scores)
+    K_out, V_out, idx, count, scores = outputs
+    desc = make_desc(Q_win, K, k_l, pool, pool_w, K_out)
+    if workspace is None:
+        workspace = alloc_workspace(desc, K.device)
+    if seq_lens is not None and (seq_lens.dtype != torch.int32 or not seq_lens.is_contiguous()):
+        raise ValueError("seq_lens must be a contiguous int32 tensor")
+    rc = load().pkv_compress_layer(ctypes.byref(desc), _p(Q_win), _p(K), _p(V), _p(seq_lens), _p(K_out), _p(V_out),
+                                   _p(idx), _p(count), _p(scores), _p(workspace), workspace.numel(),
+                                   _stream_ptr(K.device))
+    if rc != OK:
+        raise PkvError(rc, "pkv_compress_layer")
+    return outputs
+
+
+class LayersCall:
+    """Pre-marshalled arguments of pkv_compress_layers, so that a timed loop only crosses the ABI."""
+
+    def __init__(self, Q_win: Sequence[torch.Tensor], K: Sequence[torch.Tensor], V: Sequence[torch.Tensor],
+                 k_ls: Sequence[int], pool: int, pool_w: int, seq_lens: Optional[torch.Tensor] = None,
+                 want_scores: bool = False):
+        L = len(K)
+        assert len(Q_win) == L and len(V) == L and len(k_ls) == L
+        self.L = L
+        self.inputs = (list(Q_win), list(K), list(V), seq_lens)
+        self.outputs = [alloc_outputs(Q_win[l], K[l], k_ls[l], want_scores) for l in range(L)]
+        self.descs = (LayerDesc * L)(*[make_desc(Q_win[l], K[l], k_ls[l], pool, pool_w, self.outputs[l][0])
+                                        for l in range(L)])
+        self.workspace = alloc_workspace(self.descs[0], K[0].device)
+        arr = ctypes.c_void_p * L
+
+        def ptrs(ts):
+            return arr(*[None if t is None else t.data_ptr() for t in ts])
+
+        self._args = [ptrs(Q_win), ptrs(K), ptrs(V), _p(seq_lens)] + \
+                     [ptrs([o[i] for o in self.outputs]) for i in range(4)] + \
+                     [ptrs([o[4] for o in self.outputs]) if want_scores else None]
+        self.device = K[0].device
+
+    def run(self):
+        rc = load().pkv_compress_layers(self.L, self.descs, *self._args, _p(self.workspace),
+                                        self.workspace.numel(), _stream_ptr(self.device))
+        if rc != OK:
+            raise PkvError(rc, "pkv_compress_layers")
+        return self.outputs
+
+
+def compress_layers(Q_win, K, V, k_ls, pool, pool_w, seq_lens=None, want_scores=False):
+    """pkv_compress_layers: all layers of one request batch.  Returns a list of per-layer output tuples."""
+    return LayersCall(Q_win, K, V, k_ls, pool, pool_w, seq_lens, want_scores).run()

@@ -1,0 +1,241 @@
+// Host side of libpkv: budget allocation (Sec. 4.2.1), argument validation, workspace carve-up and
+// the launch sequence of one layer (Sec. 4.2.2 + gather).  Nothing here touches device memory.
+#include <math.h>
+#include <stdlib.h>
+
+#include "pkv_internal.h"
+
+namespace pkv {
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+Plan make_plan(const pkv_layer_desc& d) {
+  Plan p;
+  p.G = d.Hq / d.Hkv;
+  p.R = p.G * d.alpha;
+  p.RT = p.R <= 32 ? 1 : (p.R <= 64 ? 2 : 4);
+  p.RB = 32 * p.RT;
+  p.nrb = (p.R + p.RB - 1) / p.RB;
+  p.Rpad = p.nrb * p.RB;
+  p.BH = d.B * d.Hkv;
+  // Aim at ~4 workgroups per compute unit (256 CUs) while keeping at least one tile per wave.
+  const long long keys_total = (long long)p.BH * p.nrb * d.N;
+  long long kc = (keys_total / 1024 + 127) / 128 * 128;
+  if (kc < 128) kc = 128;
+  if (kc > 1024) kc = 1024;
+  if (const char* e = getenv("PKV_KC")) {  // tuning knob for experiments; multiple of 128
+    const long long v = atoll(e);
+    if (v >= 128 && v % 128 == 0) kc = v;
+  }
+  p.KC = (int)kc;
+  p.nchunk = (d.N + p.KC - 1) / p.KC;
+  size_t off = 0;
+  p.off_part = off;
+  off += align256((size_t)p.BH * p.Rpad * p.nchunk * sizeof(float2));
+  p.off_cfin = off;
+  off += align256((size_t)p.BH * p.Rpad * sizeof(float));
+  p.off_raw = off;
+  off += align256((size_t)p.nrb * p.BH * d.N * sizeof(float));
+  p.off_pooled = off;
+  off += align256((size_t)p.BH * d.N * sizeof(float));
+  p.total = off;
+  return p;
+}
+
+static int check_desc(const pkv_layer_desc* d) {
+  if (!d) return PKV_ERR_INVALID_ARG;
+  if (d->B < 1 || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0 || d->N < 1 || d->d < 1) return PKV_ERR_INVALID_ARG;
+  if (d->alpha < 1 || d->k_l < d->alpha) return PKV_ERR_INVALID_ARG;
+  if (d->pool != PKV_POOL_NONE && d->pool != PKV_POOL_MAX && d->pool != PKV_POOL_AVG) return PKV_ERR_INVALID_ARG;
+  if (d->pool_w < 1 || d->pool_w % 2 == 0 || d->reserved != 0) return PKV_ERR_INVALID_ARG;
+  const int64_t strides[9] = {d->q_sb, d->q_sh, d->q_st, d->kv_sb, d->kv_sh, d->kv_st, d->o_sb, d->o_sh, d->o_st};
+  for (int i = 0; i < 9; ++i)
+    if (strides[i] < 0 || strides[i] % 8 != 0) return PKV_ERR_INVALID_ARG;  // 16-byte row alignment
+  if (d->q_st < d->d || d->kv_st < d->d || d->o_st < d->d) return PKV_ERR_INVALID_ARG;
+  if (d->d != 64 && d->d != 128) return PKV_ERR_UNSUPPORTED;
+  if (d->alpha > kMaxAlpha || d->pool_w > kMaxPoolW) return PKV_ERR_UNSUPPORTED;
+  if ((int64_t)d->B * d->Hkv > 65535 || d->N > (1 << 26) || d->Hq / d->Hkv > 1024) return PKV_ERR_UNSUPPORTED;
+  return PKV_OK;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+struct LayerPtrs {
+  const void* Q;
+  const void* K;
+  const void* V;
+  void* K_out;
+  void* V_out;
+  int32_t* idx_out;
+  int32_t* count_out;
+  float* scores_out;
+};
+
+static int check_ptrs(const LayerPtrs& p) {
+  if (!p.Q || !p.K || !p.V || !p.K_out || !p.V_out || !p.idx_out || !p.count_out) return PKV_ERR_INVALID_ARG;
+  if (!aligned16(p.Q) || !aligned16(p.K) || !aligned16(p.V) || !aligned16(p.K_out) || !aligned16(p.V_out))
+    return PKV_ERR_INVALID_ARG;
+  if (((uintptr_t)p.idx_out & 3) || ((uintptr_t)p.count_out & 3) || ((uintptr_t)p.scores_out & 3))
+    return PKV_ERR_INVALID_ARG;
+  return PKV_OK;
+}
+
+static int check_workspace(const Plan& plan, const void* ws, size_t bytes) {
+  if (!ws || ((uintptr_t)ws & 255) || bytes < plan.total) return PKV_ERR_WORKSPACE;
+  return PKV_OK;
+}
+
+// Queue the kernels of one layer.  All arguments have been validated.
+static int run_layer(const pkv_layer_desc& d, const Plan& plan, const LayerPtrs& p, const int32_t* seq_lens,
+                     void* workspace, hipStream_t stream) {
+  char* ws = static_cast<char*>(workspace);
+  ScoreArgs sa;
+  sa.Q = static_cast<const uint16_t*>(p.Q);
+  sa.K = static_cast<const uint16_t*>(p.K);
+  sa.seq_lens = seq_lens;
+  sa.part = reinterpret_cast<float2*>(ws + plan.off_part);
+  sa.cfin = reinterpret_cast<float*>(ws + plan.off_cfin);
+  sa.raw = reinterpret_cast<float*>(ws + plan.off_raw);
+  sa.B = d.B; sa.Hq = d.Hq; sa.Hkv = d.Hkv; sa.G = plan.G; sa.alpha = d.alpha; sa.N = d.N; sa.k_l = d.k_l;
+  sa.R = plan.R; sa.Rpad = plan.Rpad; sa.nrb = plan.nrb; sa.KC = plan.KC; sa.nchunk = plan.nchunk;
+  sa.RT = plan.RT; sa.d = d.d;
+  sa.q_sb = d.q_sb; sa.q_sh = d.q_sh; sa.q_st = d.q_st;
+  sa.kv_sb = d.kv_sb; sa.kv_sh = d.kv_sh; sa.kv_st = d.kv_st;
+  sa.kappa = (float)(1.4426950408889634 / sqrt((double)d.d));
+
+  const int k_cap = d.k_l < d.N ? d.k_l : d.N;
+  SelectArgs se;
+  se.raw = sa.raw;
+  se.pooled = p.scores_out ? p.scores_out : reinterpret_cast<float*>(ws + plan.off_pooled);
+  se.seq_lens = seq_lens;
+  se.idx_out = p.idx_out;
+  se.count_out = p.count_out;
+  se.B = d.B; se.Hkv = d.Hkv; se.N = d.N; se.alpha = d.alpha; se.k_l = d.k_l; se.k_cap = k_cap;
+  se.nrb = plan.nrb; se.pool = (d.pool_w == 1) ? PKV_POOL_NONE : d.pool; se.pool_w = d.pool_w;
+  se.inv_G = 1.0f / (float)plan.G;
+
+  GatherArgs ga;
+  ga.K = sa.K;
+  ga.V = static_cast<const uint16_t*>(p.V);
+  ga.K_out = static_cast<uint16_t*>(p.K_out);
+  ga.V_out = static_cast<uint16_t*>(p.V_out);
+  ga.idx = p.idx_out;
+  ga.B = d.B; ga.Hkv = d.Hkv; ga.k_cap = k_cap; ga.d = d.d;
+  ga.kv_sb = d.kv_sb; ga.kv_sh = d.kv_sh; ga.kv_st = d.kv_st;
+  ga.o_sb = d.o_sb; ga.o_sh = d.o_sh; ga.o_st = d.o_st;
+
+  if (d.k_l < d.N) {  // otherwise every sequence keeps everything and no score is needed
+    if (launch_score_stats(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+    if (launch_score_finalize(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+    if (launch_score_accum(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+  }
+  if (launch_pool_select(se, stream) != hipSuccess) return PKV_ERR_HIP;
+  if (launch_gather(ga, stream) != hipSuccess) return PKV_ERR_HIP;
+  return PKV_OK;
+}
+
+}  // namespace pkv
+
+using namespace pkv;
+
+extern "C" {
+
+int pkv_budgets(int32_t L, int32_t avg_budget, int32_t beta, int32_t alpha, int32_t* k_out) {
+  if (L < 1 || beta < 1 || alpha < 0 || avg_budget < alpha || !k_out) return PKV_ERR_INVALID_ARG;
+  const int64_t A = (int64_t)avg_budget - alpha;  // per-layer budget left after the window
+  if (L == 1) {
+    k_out[0] = avg_budget;
+    return PKV_OK;
+  }
+  // r_l = A * [(2 beta - 1)(L - 1) - 2 (beta - 1) l] / (beta (L - 1)): from A/beta at the top layer to
+  // 2A - A/beta at the bottom one.  Work on the integer numerators over the common denominator.
+  const int64_t den = (int64_t)beta * (L - 1);
+  int64_t floor_sum = 0;
+  for (int32_t l = 0; l < L; ++l) {
+    const int64_t num = A * ((2 * (int64_t)beta - 1) * (L - 1) - 2 * ((int64_t)beta - 1) * l);
+    k_out[l] = (int32_t)(num / den);
+    floor_sum += num / den;
+  }
+  // The fractional parts sum to an integer `extra` < L.  Give one unit each to the `extra` layers with
+  // the largest fraction; among equal fractions the lower layer goes first.
+  const int64_t extra = (int64_t)L * A - floor_sum;
+  for (int64_t given = 0; given < extra; ++given) {
+    int32_t pick = -1;
+    int64_t pick_frac = -1;
+    for (int32_t l = 0; l < L; ++l) {
+      const int64_t num = A * ((2 * (int64_t)beta - 1) * (L - 1) - 2 * ((int64_t)beta - 1) * l);
+      if (k_out[l] != (int32_t)(num / den)) continue;  // already bumped
+      if (num % den > pick_frac) {
+        pick_frac = num % den;
+        pick = l;
+      }
+    }
+    k_out[pick] += 1;
+  }
+  for (int32_t l = 0; l < L; ++l) k_out[l] += alpha;
+  return PKV_OK;
+}
+
+size_t pkv_workspace_bytes(const pkv_layer_desc* desc) {
+  if (check_desc(desc) != PKV_OK) return 0;
+  return make_plan(*desc).total;
+}
+
+int pkv_compress_layer(const pkv_layer_desc* desc, const void* Q_win, const void* K, const void* V,
+                       const int32_t* seq_lens, void* K_out, void* V_out, int32_t* idx_out, int32_t* count_out,
+                       float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc != PKV_OK) return rc;
+  const LayerPtrs p = {Q_win, K, V, K_out, V_out, idx_out, count_out, scores_out};
+  rc = check_ptrs(p);
+  if (rc != PKV_OK) return rc;
+  if ((uintptr_t)seq_lens & 3) return PKV_ERR_INVALID_ARG;
+  const Plan plan = make_plan(*desc);
+  rc = check_workspace(plan, workspace, workspace_bytes);
+  if (rc != PKV_OK) return rc;
+  return run_layer(*desc, plan, p, seq_lens, workspace, static_cast<hipStream_t>(stream));
+}
+
+int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win, const void* const* K,
+                        const void* const* V, const int32_t* seq_lens, void* const* K_out, void* const* V_out,
+                        int32_t* const* idx_out, int32_t* const* count_out, float* const* scores_out,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (L < 1 || !descs || !Q_win || !K || !V || !K_out || !V_out || !idx_out || !count_out) return PKV_ERR_INVALID_ARG;
+  if ((uintptr_t)seq_lens & 3) return PKV_ERR_INVALID_ARG;
+  for (int32_t l = 0; l < L; ++l) {
+    int rc = check_desc(&descs[l]);
+    if (rc != PKV_OK) return rc;
+    const pkv_layer_desc &a = descs[0], &b = descs[l];
+    if (a.B != b.B || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.N != b.N || a.alpha != b.alpha ||
+        a.pool != b.pool || a.pool_w != b.pool_w || a.q_sb != b.q_sb || a.q_sh != b.q_sh || a.q_st != b.q_st ||
+        a.kv_sb != b.kv_sb || a.kv_sh != b.kv_sh || a.kv_st != b.kv_st)
+      return PKV_ERR_INVALID_ARG;
+    const LayerPtrs p = {Q_win[l], K[l], V[l], K_out[l], V_out[l], idx_out[l], count_out[l],
+                         scores_out ? scores_out[l] : nullptr};
+    rc = check_ptrs(p);
+    if (rc != PKV_OK) return rc;
+  }
+  const Plan plan = make_plan(descs[0]);
+  int rc = check_workspace(plan, workspace, workspace_bytes);
+  if (rc != PKV_OK) return rc;
+  for (int32_t l = 0; l < L; ++l) {
+    const LayerPtrs p = {Q_win[l], K[l], V[l], K_out[l], V_out[l], idx_out[l], count_out[l],
+                         scores_out ? scores_out[l] : nullptr};
+    rc = run_layer(descs[l], plan, p, seq_lens, workspace, static_cast<hipStream_t>(stream));
+    if (rc != PKV_OK) return rc;
+  }
+  return PKV_OK;
+}
+
+const char* pkv_status_string(int status) {
+  switch (status) {
+    case PKV_OK: return "ok";
+    case PKV_ERR_INVALID_ARG: return "invalid argument";
+    case PKV_ERR_UNSUPPORTED: return "unsupported shape";
+    case PKV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case PKV_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

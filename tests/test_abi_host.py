@@ -1,0 +1,118 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/pkv.h declares, computes the
+budgets of Sec. 4.2.1 exactly like the oracle, and rejects bad arguments before any launch (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import pkv_oracle
+from paper_2406_02069_amd import binding
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "pkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pkv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = binding.load()
+    names = _declared()
+    assert names == sorted(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    assert binding.status_string(0) == "ok"
+    for s in range(1, 5):
+        assert binding.status_string(s) not in ("ok", "unknown status")
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_budgets_equal_oracle_on_golden_and_grid():
+    with open(os.path.join(HERE, "golden", "budget_cases.txt")) as f:
+        for line in f:
+            if line.startswith("#"):
+                continue
+            head, tail = line.split(":")
+            L, avg, beta, alpha = (int(x) for x in head.split())
+            assert binding.budgets(L, avg, beta, alpha) == [int(x) for x in tail.split()]
+    rs = np.random.RandomState(0)
+    for _ in range(300):
+        L = int(rs.randint(1, 100))
+        alpha = int(rs.randint(0, 70))
+        avg = alpha + int(rs.randint(0, 3000))
+        beta = int(rs.randint(1, 40))
+        assert binding.budgets(L, avg, beta, alpha) == list(pkv_oracle.budgets(L, avg, beta, alpha))
+
+
+def test_budgets_reject_bad_arguments():
+    for bad in [(0, 10, 20, 8), (4, 10, 0, 8), (4, 7, 20, 8), (4, 10, 20, -1)]:
+        with pytest.raises(binding.PkvError) as e:
+            binding.budgets(*bad)
+        assert e.value.status == binding.ERR_INVALID_ARG
+    assert binding.load().pkv_budgets(4, 128, 20, 8, None) == binding.ERR_INVALID_ARG
+
+
+def _desc(**kw):
+    base = dict(B=1, Hq=32, Hkv=8, d=128, N=4096, alpha=8, k_l=128, pool=1, pool_w=7, reserved=0,
+                q_sb=32 * 8 * 128, q_sh=8 * 128, q_st=128, kv_sb=8 * 4096 * 128, kv_sh=4096 * 128, kv_st=128,
+                o_sb=8 * 128 * 128, o_sh=128 * 128, o_st=128)
+    base.update(kw)
+    return binding.LayerDesc(**base)
+
+
+def _call(desc, ws_bytes=None, ws=0x10000, **ptr_overrides):
+    lib = binding.load()
+    p = dict(Q=0x1000, K=0x2000, V=0x3000, seq=None, Ko=0x4000, Vo=0x5000, idx=0x6000, cnt=0x7000, sc=None)
+    p.update(ptr_overrides)
+    if ws_bytes is None:
+        ws_bytes = binding.workspace_bytes(desc)
+    return lib.pkv_compress_layer(ctypes.byref(desc), p["Q"], p["K"], p["V"], p["seq"], p["Ko"], p["Vo"], p["idx"],
+                                  p["cnt"], p["sc"], ws, ws_bytes, None)
+
+
+def test_workspace_size_is_positive_and_budget_independent():
+    a = binding.workspace_bytes(_desc(k_l=64))
+    b = binding.workspace_bytes(_desc(k_l=4000))
+    assert a == b > 0
+    assert binding.workspace_bytes(_desc(Hq=30)) == 0        # Hq % Hkv != 0
+    assert binding.workspace_bytes(_desc(d=96)) == 0          # unsupported head dim
+
+
+def test_compress_layer_rejects_bad_arguments_before_launching():
+    I, U, W = binding.ERR_INVALID_ARG, binding.ERR_UNSUPPORTED, binding.ERR_WORKSPACE
+    assert _call(_desc(Hq=30)) == I
+    assert _call(_desc(k_l=4)) == I                 # budget smaller than the window
+    assert _call(_desc(alpha=0, k_l=8)) == I
+    assert _call(_desc(pool=7)) == I
+    assert _call(_desc(pool_w=4)) == I
+    assert _call(_desc(reserved=1)) == I
+    assert _call(_desc(kv_st=130)) == I             # rows not 16-byte aligned
+    assert _call(_desc(kv_st=64)) == I              # rows overlap
+    assert _call(_desc(d=96, q_st=96, kv_st=96, o_st=96)) == U
+    assert _call(_desc(alpha=72, k_l=128)) == U
+    assert _call(_desc(pool_w=65)) == U
+    good = _desc()
+    assert _call(good, Q=None) == I
+    assert _call(good, idx=None) == I
+    assert _call(good, K=0x2004) == I               # misaligned pointer
+    assert _call(good, ws=None) == W
+    assert _call(good, ws=0x10010) == W             # not 256-byte aligned
+    assert _call(good, ws_bytes=binding.workspace_bytes(good) - 1) == W
+
+
+def test_compress_layers_rejects_mismatched_layers():
+    lib = binding.load()
+    descs = (binding.LayerDesc * 2)(_desc(), _desc(N=2048, kv_sh=2048 * 128, kv_sb=8 * 2048 * 128))
+    arr = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    rc = lib.pkv_compress_layers(2, descs, arr, arr, arr, None, arr, arr, arr, arr, None, 0x10000, 1 << 30, None)
+    assert rc == binding.ERR_INVALID_ARG
+    rc = lib.pkv_compress_layers(0, descs, arr, arr, arr, None, arr, arr, arr, arr, None, 0x10000, 1 << 30, None)
+    assert rc == binding.ERR_INVALID_ARG

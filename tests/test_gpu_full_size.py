@@ -1,0 +1,63 @@
+"""Full-size configurations, in the launch configuration the benchmark times (pkv_compress_layers over real
+shapes), checked against the oracle on sampled layers: first, last, one middle, one seeded-random."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2406_02069_amd import binding, synth
+from tests.parity import compare_layer
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _sample_layers(w, k):
+    rs = np.random.RandomState(w.index + 17)
+    cand = [0, w.L - 1, w.L // 2, int(rs.randint(1, w.L - 1))]
+    out = []
+    for c in cand:
+        if c not in out:
+            out.append(c)
+    return out[:k]
+
+
+def _full(cfg, n_layers, avg=None):
+    w = synth.WORKLOADS[cfg]
+    avg = avg or w.avg_budgets[0]
+    ks = binding.budgets(w.L, avg, w.beta, w.alpha)
+    sel = _sample_layers(w, n_layers)
+    layers = [synth.make_layer(w, l, DEV) for l in sel]
+    lens = layers[0][3]
+    lens_dev = None if lens is None else torch.from_numpy(lens).to(DEV)
+    outs = binding.compress_layers([x[0] for x in layers], [x[1] for x in layers], [x[2] for x in layers],
+                                   [ks[l] for l in sel], w.pool, w.pool_w, seq_lens=lens_dev, want_scores=True)
+    torch.cuda.synchronize()
+    tot = dict(units=0, near_tie_units=0)
+    for (Q, K, V, _), l, out in zip(layers, sel, outs):
+        print(f"config {cfg} layer {l} k_l {ks[l]}: oracle ...", flush=True)
+        st = compare_layer(Q, K, V, ks[l], w.alpha, w.pool, w.pool_w, lens, out)
+        print("   ", st, flush=True)
+        tot["units"] += st["units"]
+        tot["near_tie_units"] += st["near_tie_units"]
+    assert tot["near_tie_units"] <= max(1, tot["units"] // 10)
+    return tot
+
+
+def test_config1_llama3_8b_8k():
+    _full(1, 4)
+
+
+def test_config2_llama3_8b_32k_avg128():
+    _full(2, 2)
+
+
+def test_config2_llama3_8b_32k_avg2048():
+    _full(2, 1, avg=2048)
+
+
+def test_config3_mistral_ragged_batch():
+    _full(3, 1)
+
+
+def test_config4_llama3_70b_32k():
+    _full(4, 1)

@@ -1,0 +1,155 @@
+"""HIP library vs. CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pkv_oracle
+from paper_2406_02069_amd import binding, synth
+from tests.parity import bits, compare_layer
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _lens_dev(lens):
+    return None if lens is None else torch.from_numpy(np.asarray(lens, dtype=np.int32)).to(DEV)
+
+
+def _run_and_compare(w, layer, k_l, Q=None, K=None, V=None, lens=None, check_scores=True):
+    if Q is None:
+        Q, K, V, lens = synth.make_layer(w, layer, DEV)
+    out = binding.compress_layer(Q, K, V, k_l, w.pool, w.pool_w, seq_lens=_lens_dev(lens), want_scores=True)
+    torch.cuda.synchronize()
+    return compare_layer(Q, K, V, k_l, w.alpha, w.pool, w.pool_w, lens, out, check_scores=check_scores), out
+
+
+def _rand(B, Hq, Hkv, d, N, alpha, seed):
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    Q = torch.randn(B, Hq, alpha, d, generator=g, device=DEV).to(torch.bfloat16)
+    K = torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    return Q, K, V
+
+
+class _W:  # minimal stand-in for a workload in ad-hoc cases
+    def __init__(self, alpha, pool, pool_w):
+        self.alpha, self.pool, self.pool_w = alpha, pool, pool_w
+
+
+def test_config0_tiny_mha_all_layers():
+    w = synth.WORKLOADS[0]
+    ks = binding.budgets(w.L, w.avg_budgets[0], w.beta, w.alpha)
+    assert ks == [242, 166, 90, 14]
+    for layer in range(w.L):
+        print("config0 layer", layer, flush=True)
+        st, _ = _run_and_compare(w, layer, ks[layer])
+        assert st["units"] == 8
+
+
+@pytest.mark.parametrize("cfg,N", [(1, 1500), (1, 4099), (2, 2500), (4, 1111)])
+def test_scaled_configs_ragged_tiles(cfg, N):
+    # several key tiles, several chunks, a ragged tail (N not a multiple of 32), every row-block shape
+    w = synth.WORKLOADS[cfg].scaled(N=N, L=3)
+    ks = binding.budgets(w.L, w.avg_budgets[0], w.beta, w.alpha)
+    for layer in range(w.L):
+        print("scaled config", cfg, "N", N, "layer", layer, flush=True)
+        _run_and_compare(w, layer, ks[layer])
+
+
+def test_config3_scaled_ragged_batch_with_nan_padding():
+    w = synth.WORKLOADS[3].scaled(N=3000, ragged_min=700, B=4)
+    ks = binding.budgets(w.L, w.avg_budgets[0], w.beta, w.alpha)
+    for layer, k_l in ((0, ks[0]), (1, ks[-1]), (2, 900)):     # 900 > some n_b: those keep everything
+        print("config3 scaled layer", layer, flush=True)
+        st, out = _run_and_compare(w, layer, k_l)
+        assert not torch.isnan(out[4]).any()
+
+
+@pytest.mark.parametrize("d,Hq,Hkv,alpha", [(64, 8, 8, 8), (64, 16, 2, 8), (64, 12, 4, 5), (128, 4, 4, 1),
+                                             (128, 28, 4, 16), (128, 64, 8, 64), (64, 6, 2, 37)])
+def test_head_geometries(d, Hq, Hkv, alpha):
+    Q, K, V = _rand(2, Hq, Hkv, d, 777, alpha, seed=d + Hq + alpha)
+    for pool, pw in ((synth.POOL_MAX, 7), (synth.POOL_AVG, 5), (synth.POOL_NONE, 1), (synth.POOL_MAX, 63)):
+        print("geometry", d, Hq, Hkv, alpha, pool, pw, flush=True)
+        _run_and_compare(_W(alpha, pool, pw), 0, alpha + 100, Q, K, V)
+
+
+def test_edge_budgets_and_lengths():
+    alpha = 8
+    Q, K, V = _rand(3, 8, 2, 128, 300, alpha, seed=5)
+    w = _W(alpha, synth.POOL_MAX, 7)
+    for k_l in (alpha, alpha + 1, 299, 300, 301, 5000):        # window only ... full cache
+        print("edge k_l", k_l, flush=True)
+        _run_and_compare(w, 0, k_l, Q, K, V)
+    lens = np.array([300, 3, 0], dtype=np.int32)               # n < alpha and n = 0
+    for k_l in (alpha, 40):
+        print("edge lens k_l", k_l, flush=True)
+        _run_and_compare(w, 0, k_l, Q, K, V, lens)
+    lens = np.array([alpha + 1, 41, 40], dtype=np.int32)       # single prefix token; n = k_l + 1; n = k_l
+    _run_and_compare(w, 0, 40, Q, K, V, lens)
+
+
+def test_exact_ties_lower_position_wins():
+    # identical keys -> identical scores everywhere: the kept prefix must be 0..kk-1
+    alpha, N = 4, 500
+    Q, K, V = _rand(1, 4, 2, 64, N, alpha, seed=6)
+    K[:] = K[:, :, :1, :]
+    w = _W(alpha, synth.POOL_NONE, 1)
+    st, out = _run_and_compare(w, 0, 54, Q, K, V)
+    assert out[2][0, 0, :50].tolist() == list(range(50))
+    # max-pool plateaus cut in the middle
+    Q, K, V = _rand(1, 4, 1, 64, N, alpha, seed=7)
+    K[0, 0, 200] = (Q[0, :, :].float().sum(dim=(0, 1)) * 2).to(torch.bfloat16)
+    st, out = _run_and_compare(_W(alpha, synth.POOL_MAX, 7), 0, alpha + 4, Q, K, V)
+    assert out[2][0, 0, :4].tolist() == [197, 198, 199, 200]
+
+
+def test_strided_inputs_and_outputs():
+    # K/V stored token-major [B, N, Hkv, d] and viewed head-major; outputs written into a larger buffer
+    alpha, N, B, Hq, Hkv, d, k_l = 8, 600, 2, 8, 2, 128, 64
+    g = torch.Generator(device=DEV).manual_seed(8)
+    Q = torch.randn(B, alpha, Hq, d, generator=g, device=DEV).to(torch.bfloat16).permute(0, 2, 1, 3)
+    K = torch.randn(B, N, Hkv, d, generator=g, device=DEV).to(torch.bfloat16).permute(0, 2, 1, 3)
+    V = torch.randn(B, N, Hkv, d, generator=g, device=DEV).to(torch.bfloat16).permute(0, 2, 1, 3)
+    big = torch.zeros(B, Hkv, k_l + 10, 2 * d, dtype=torch.bfloat16, device=DEV)
+    K_out, V_out = big[:, :, :k_l, :d], big[:, :, :k_l, d:]
+    _, _, idx, count, scores = binding.alloc_outputs(Q, K, k_l, want_scores=True)
+    out = binding.compress_layer(Q, K, V, k_l, synth.POOL_MAX, 7, outputs=(K_out, V_out, idx, count, scores))
+    torch.cuda.synchronize()
+    compare_layer(Q, K, V, k_l, alpha, synth.POOL_MAX, 7, None, out)
+    assert torch.all(big[:, :, k_l:] == 0)
+
+
+def test_deterministic_and_inputs_untouched():
+    w = synth.WORKLOADS[1].scaled(N=5000, L=1)
+    Q, K, V, _ = synth.make_layer(w, 0, DEV)
+    q0, k0, v0 = bits(Q).copy(), bits(K).copy(), bits(V).copy()
+    a = binding.compress_layer(Q, K, V, 100, w.pool, w.pool_w, want_scores=True)
+    b = binding.compress_layer(Q, K, V, 100, w.pool, w.pool_w, want_scores=True)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.int32) if x.dtype == torch.float32 else x,
+                           y.view(torch.int32) if y.dtype == torch.float32 else y)
+    assert np.array_equal(bits(Q), q0) and np.array_equal(bits(K), k0) and np.array_equal(bits(V), v0)
+
+
+def test_compress_layers_equals_per_layer_calls_and_budget_nesting():
+    w = synth.WORKLOADS[2].scaled(N=3000, L=4)
+    layers = [synth.make_layer(w, l, DEV) for l in range(w.L)]
+    Qs, Ks, Vs = [x[0] for x in layers], [x[1] for x in layers], [x[2] for x in layers]
+    prev = None
+    for avg in (64, 128, 512):
+        ks = binding.budgets(w.L, avg, w.beta, w.alpha)
+        outs = binding.compress_layers(Qs, Ks, Vs, ks, w.pool, w.pool_w, want_scores=True)
+        torch.cuda.synchronize()
+        for l in range(w.L):
+            single = binding.compress_layer(Qs[l], Ks[l], Vs[l], ks[l], w.pool, w.pool_w, want_scores=True)
+            torch.cuda.synchronize()
+            for x, y in zip(outs[l], single):
+                assert torch.equal(x, y)
+        compare_layer(Qs[0], Ks[0], Vs[0], ks[0], w.alpha, w.pool, w.pool_w, None, outs[0])
+        # same scores, larger budget (layer 0 budgets grow with avg) => kept sets are nested
+        cur = [set(outs[0][2][0, g].tolist()) for g in range(w.Hkv)]
+        if prev is not None:
+            assert all(p <= c for p, c in zip(prev, cur))
+        prev = cur

@@ -1,0 +1,149 @@
+"""Benchmark of the PyramidKV compression step on one MI355X.
+
+A step = the whole hot path (budgets excluded: host, once) over one request batch: pkv_compress_layers over all L
+layers of the workload -- window scoring, pooling, per-head top-k, K/V gather.  Inputs are resident in HBM.
+Prints one JSON line (metric of the benchmark spec: compressed prefill tokens/s over all layers).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published
+
+
+def layer_bytes(w, k_l, sum_n):
+    """Algorithmic bytes of one layer: K once + Q_win + gathered K,V rows read and written + kept indices."""
+    k_bytes = w.Hkv * sum_n * w.d * 2
+    q_bytes = w.B * w.Hq * w.alpha * w.d * 2
+    gather = 4 * w.B * w.Hkv * k_l * w.d * 2
+    idx = w.B * w.Hkv * k_l * 4
+    return k_bytes + q_bytes + gather + idx
+
+
+def score_sweep_bytes(w, sum_n):
+    """Algorithmic bytes of one scoring sweep launch: the layer's K once plus Q_win."""
+    return w.Hkv * sum_n * w.d * 2 + w.B * w.Hq * w.alpha * w.d * 2
+
+
+def cpu_baseline(w, ks, layers_host, lens, budget_s=15.0):
+    """The oracle, as it stands, on the host cores, on a bounded sample of layers of the same workload."""
+    from oracle import pkv_oracle
+    sum_n = int(lens.sum()) if lens is not None else w.B * w.N
+    t_used, done = 0.0, []
+    order = [0, w.L - 1] + [l for l in range(1, w.L - 1)]
+    for l in order:
+        if l not in layers_host:
+            continue
+        Q, K, V = layers_host[l]
+        t0 = time.perf_counter()
+        pkv_oracle.compress_layer(Q, K, V, ks[l], w.alpha, w.pool, w.pool_w, seq_lens=lens, want_pooled=False)
+        t_used += time.perf_counter() - t0
+        done.append(l)
+        if t_used > budget_s:
+            break
+    per_layer = t_used / len(done)
+    threads = min(pkv_oracle.num_threads(), w.G * w.alpha)
+    return {"value": sum_n / (per_layer * w.L), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"layers {sorted(done)} of {w.L} timed ({t_used:.1f} s), all-layer time extrapolated linearly"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: the 32k config)")
+    ap.add_argument("--avg-budget", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2406_02069_amd import binding, synth
+
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.config]
+    avg = args.avg_budget or w.avg_budgets[0]
+    ks = binding.budgets(w.L, avg, w.beta, w.alpha)
+    lens = synth.seq_lens(w)
+    sum_n = int(lens.sum()) if lens is not None else w.B * w.N
+    lens_dev = None if lens is None else torch.from_numpy(lens).to(dev)
+
+    # all layers resident in HBM; a bounded set of layers is also kept on the host for the oracle
+    n_host = 0 if args.no_cpu_baseline else min(w.L, 8)
+    host_ids = sorted(set([0, w.L - 1] + list(range(1, w.L - 1))[: max(n_host - 2, 0)])) if n_host else []
+    Qs, Ks, Vs, layers_host = [], [], [], {}
+    for l in range(w.L):
+        Q, K, V, _ = synth.make_layer(w, l, dev)
+        Qs.append(Q), Ks.append(K), Vs.append(V)
+        if l in host_ids:
+            layers_host[l] = (Q.cpu(), K.cpu(), V.cpu())
+    call = binding.LayersCall(Qs, Ks, Vs, ks, w.pool, w.pool_w, seq_lens=lens_dev)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        call.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        call.run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # Per-kernel device time: the same steps again, with HIP events around every kernel (recorded on the stream the
+    # kernels run on).  Kept apart from the timed region above so that the event packets do not slow `value`.
+    events = binding.HipEvents(5 * w.L + 1)
+    per_kernel = {}
+    for _ in range(args.steps):
+        ids = binding.run_profiled(call, events)
+        torch.cuda.synchronize()
+        for i, kid in enumerate(ids):
+            per_kernel.setdefault(kid, []).append(events.elapsed_ms(i, i + 1))
+    events.close()
+    avg_ms = {binding.KERNEL_NAMES[k]: float(np.mean(v)) for k, v in per_kernel.items()}
+    sum_ms = {binding.KERNEL_NAMES[k]: float(np.sum(v)) / args.steps for k, v in per_kernel.items()}
+    dominant = max(sum_ms, key=sum_ms.get)
+
+    total_bytes = sum(layer_bytes(w, k, sum_n) for k in ks)
+    sweep_bytes = score_sweep_bytes(w, sum_n)
+    achieved = sweep_bytes / (avg_ms[dominant] * 1e-3) / 1e9 if dominant.startswith("score_") else None
+    out = {
+        "metric": "compressed prefill tokens/sec (all layers, select+gather); achieved HBM GB/s",
+        "value": sum_n / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: B{w.B} L{w.L} Hq{w.Hq} Hkv{w.Hkv} d{w.d} N{w.N} alpha{w.alpha} "
+                               f"avg_budget{avg} beta{w.beta} pool{w.pool}/w{w.pool_w}",
+                   "tokens_per_step": sum_n, "algorithmic_bytes_per_step": total_bytes},
+        "whole_path": {"achieved_GBps": total_bytes / (ms_per_step * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+        "roofline": {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": None if achieved is None else achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": sweep_bytes, "avg_launch_ms": avg_ms[dominant]},
+        "kernel_ms_per_step": sum_ms,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, ks, layers_host, lens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

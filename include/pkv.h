@@ -174,6 +174,38 @@ int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs,
                         float* const* scores_out, void* workspace,
                         size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid (no part of the method): pkv_compress_layers with the
+ * caller's HIP events recorded around the kernels, so that a benchmark can
+ * attribute device time to each kernel without a profiler.
+ *
+ * events     HOST array of n_events hipEvent_t handles created by the caller
+ *            with timing enabled.  events[0] is recorded on `stream` before
+ *            the first kernel, events[i] after the i-th kernel launched.
+ * kernel_ids HOST int32[n_events - 1], written: kernel_ids[i-1] is the
+ *            pkv_kernel_id of the kernel between events[i-1] and events[i].
+ * n_used     HOST int32, written: number of events recorded (kernels + 1).
+ * The call does not synchronise; the caller synchronises the stream and
+ * reads hipEventElapsedTime(events[i-1], events[i]).
+ * Errors: as pkv_compress_layers; n_events too small for the launch
+ * sequence (5 kernels per layer + 1) -> PKV_ERR_INVALID_ARG.
+ */
+typedef enum {
+  PKV_KERNEL_SCORE_STATS = 0, /* sweep 1 over K: per-row softmax statistics */
+  PKV_KERNEL_SCORE_FINALIZE = 1,
+  PKV_KERNEL_SCORE_ACCUM = 2, /* sweep 2 over K: per-key window scores      */
+  PKV_KERNEL_POOL_SELECT = 3,
+  PKV_KERNEL_GATHER = 4
+} pkv_kernel_id;
+
+int pkv_compress_layers_profiled(
+    int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
+    const void* const* K, const void* const* V, const int32_t* seq_lens,
+    void* const* K_out, void* const* V_out, int32_t* const* idx_out,
+    int32_t* const* count_out, float* const* scores_out, void* workspace,
+    size_t workspace_bytes, void* stream, void* const* events,
+    int32_t n_events, int32_t* kernel_ids, int32_t* n_used);
+
 /* Static, NUL-terminated description of a pkv_status value.  HOST only. */
 const char* pkv_status_string(int status);
 

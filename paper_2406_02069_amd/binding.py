@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libpkv.so")
 POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
-EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers", "pkv_status_string"]
+EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers",
+           "pkv_compress_layers_profiled", "pkv_status_string"]
 
 
 class PkvError(RuntimeError):
@@ -182,3 +183,55 @@ class LayersCall:
 def compress_layers(Q_win, K, V, k_ls, pool, pool_w, seq_lens=None, want_scores=False):
     """pkv_compress_layers: all layers of one request batch.  Returns a list of per-layer output tuples."""
     return LayersCall(Q_win, K, V, k_ls, pool, pool_w, seq_lens, want_scores).run()
+
+
+KERNEL_NAMES = ["score_stats", "score_finalize", "score_accum", "pool_select", "gather"]
+
+
+class HipEvents:
+    """A pool of timing-enabled HIP events (created through the HIP runtime that torch has loaded)."""
+
+    def __init__(self, n: int):
+        self.hip = ctypes.CDLL("libamdhip64.so.7")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.n = n
+        self.handles = (ctypes.c_void_p * n)()
+        for i in range(n):
+            ev = ctypes.c_void_p()
+            if self.hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.handles[i] = ev
+
+    def elapsed_ms(self, i: int, j: int) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.handles[i], self.handles[j])
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
+
+    def close(self):
+        for i in range(self.n):
+            self.hip.hipEventDestroy(self.handles[i])
+        self.n = 0
+
+
+def run_profiled(call: LayersCall, events: HipEvents):
+    """pkv_compress_layers_profiled on the current stream.  Returns the kernel ids of the recorded intervals;
+    after a stream synchronise, interval i lies between events i and i+1."""
+    lib = load()
+    if not hasattr(lib, "_prof_ready"):
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        lib.pkv_compress_layers_profiled.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 10 + \
+            [ctypes.c_size_t, vp, vp, i32, vp, vp]
+        lib.pkv_compress_layers_profiled.restype = ctypes.c_int
+        lib._prof_ready = True
+    ids = (ctypes.c_int32 * events.n)()
+    used = ctypes.c_int32(0)
+    rc = lib.pkv_compress_layers_profiled(call.L, call.descs, *call._args, _p(call.workspace),
+                                          call.workspace.numel(), _stream_ptr(call.device), events.handles,
+                                          events.n, ids, ctypes.byref(used))
+    if rc != OK:
+        raise PkvError(rc, "pkv_compress_layers_profiled")
+    return [int(ids[i]) for i in range(used.value - 1)]

@@ -85,9 +85,31 @@ static int check_workspace(const Plan& plan, const void* ws, size_t bytes) {
   return PKV_OK;
 }
 
+// Optional event trail for pkv_compress_layers_profiled.
+struct Recorder {
+  void* const* events;
+  int32_t n_events;
+  int32_t* kernel_ids;
+  int32_t used;
+  bool overflow;
+  void begin(hipStream_t s) {
+    used = 0;
+    overflow = n_events < 1;
+    if (!overflow) hipEventRecord(static_cast<hipEvent_t>(events[used++]), s);
+  }
+  void after(int id, hipStream_t s) {
+    if (used >= n_events) {
+      overflow = true;
+      return;
+    }
+    kernel_ids[used - 1] = id;
+    hipEventRecord(static_cast<hipEvent_t>(events[used++]), s);
+  }
+};
+
 // Queue the kernels of one layer.  All arguments have been validated.
 static int run_layer(const pkv_layer_desc& d, const Plan& plan, const LayerPtrs& p, const int32_t* seq_lens,
-                     void* workspace, hipStream_t stream) {
+                     void* workspace, hipStream_t stream, Recorder* rec = nullptr) {
   char* ws = static_cast<char*>(workspace);
   ScoreArgs sa;
   sa.Q = static_cast<const uint16_t*>(p.Q);
@@ -126,11 +148,16 @@ static int run_layer(const pkv_layer_desc& d, const Plan& plan, const LayerPtrs&
 
   if (d.k_l < d.N) {  // otherwise every sequence keeps everything and no score is needed
     if (launch_score_stats(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+    if (rec) rec->after(PKV_KERNEL_SCORE_STATS, stream);
     if (launch_score_finalize(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+    if (rec) rec->after(PKV_KERNEL_SCORE_FINALIZE, stream);
     if (launch_score_accum(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+    if (rec) rec->after(PKV_KERNEL_SCORE_ACCUM, stream);
   }
   if (launch_pool_select(se, stream) != hipSuccess) return PKV_ERR_HIP;
+  if (rec) rec->after(PKV_KERNEL_POOL_SELECT, stream);
   if (launch_gather(ga, stream) != hipSuccess) return PKV_ERR_HIP;
+  if (rec) rec->after(PKV_KERNEL_GATHER, stream);
   return PKV_OK;
 }
 
@@ -196,10 +223,11 @@ int pkv_compress_layer(const pkv_layer_desc* desc, const void* Q_win, const void
   return run_layer(*desc, plan, p, seq_lens, workspace, static_cast<hipStream_t>(stream));
 }
 
-int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win, const void* const* K,
-                        const void* const* V, const int32_t* seq_lens, void* const* K_out, void* const* V_out,
-                        int32_t* const* idx_out, int32_t* const* count_out, float* const* scores_out,
-                        void* workspace, size_t workspace_bytes, void* stream) {
+static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
+                                const void* const* K, const void* const* V, const int32_t* seq_lens,
+                                void* const* K_out, void* const* V_out, int32_t* const* idx_out,
+                                int32_t* const* count_out, float* const* scores_out, void* workspace,
+                                size_t workspace_bytes, void* stream, Recorder* rec) {
   if (L < 1 || !descs || !Q_win || !K || !V || !K_out || !V_out || !idx_out || !count_out) return PKV_ERR_INVALID_ARG;
   if ((uintptr_t)seq_lens & 3) return PKV_ERR_INVALID_ARG;
   for (int32_t l = 0; l < L; ++l) {
@@ -218,13 +246,41 @@ int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs, const void* cons
   const Plan plan = make_plan(descs[0]);
   int rc = check_workspace(plan, workspace, workspace_bytes);
   if (rc != PKV_OK) return rc;
+  if (rec) {
+    if (!rec->events || !rec->kernel_ids || rec->n_events < 5 * L + 1) return PKV_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < 5 * L + 1; ++i)
+      if (!rec->events[i]) return PKV_ERR_INVALID_ARG;
+    rec->begin(static_cast<hipStream_t>(stream));
+  }
   for (int32_t l = 0; l < L; ++l) {
     const LayerPtrs p = {Q_win[l], K[l], V[l], K_out[l], V_out[l], idx_out[l], count_out[l],
                          scores_out ? scores_out[l] : nullptr};
-    rc = run_layer(descs[l], plan, p, seq_lens, workspace, static_cast<hipStream_t>(stream));
+    rc = run_layer(descs[l], plan, p, seq_lens, workspace, static_cast<hipStream_t>(stream), rec);
     if (rc != PKV_OK) return rc;
   }
   return PKV_OK;
+}
+
+int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win, const void* const* K,
+                        const void* const* V, const int32_t* seq_lens, void* const* K_out, void* const* V_out,
+                        int32_t* const* idx_out, int32_t* const* count_out, float* const* scores_out,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  return compress_layers_impl(L, descs, Q_win, K, V, seq_lens, K_out, V_out, idx_out, count_out, scores_out,
+                              workspace, workspace_bytes, stream, nullptr);
+}
+
+int pkv_compress_layers_profiled(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
+                                 const void* const* K, const void* const* V, const int32_t* seq_lens,
+                                 void* const* K_out, void* const* V_out, int32_t* const* idx_out,
+                                 int32_t* const* count_out, float* const* scores_out, void* workspace,
+                                 size_t workspace_bytes, void* stream, void* const* events, int32_t n_events,
+                                 int32_t* kernel_ids, int32_t* n_used) {
+  if (!n_used) return PKV_ERR_INVALID_ARG;
+  Recorder rec = {events, n_events, kernel_ids, 0, false};
+  const int rc = compress_layers_impl(L, descs, Q_win, K, V, seq_lens, K_out, V_out, idx_out, count_out,
+                                      scores_out, workspace, workspace_bytes, stream, &rec);
+  *n_used = rec.used;
+  return rc;
 }
 
 const char* pkv_status_string(int status) {

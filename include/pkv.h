@@ -91,11 +91,12 @@ typedef struct {
 } pkv_layer_desc;
 
 /*
- * Bytes of DEVICE workspace pkv_compress_layer needs for this shape (also
- * enough for pkv_compress_layers over layers of this shape with any k_l).
- * HOST only, pure.  Returns 0 if the descriptor is invalid.
+ * Bytes of DEVICE workspace needed to compress L layers of this shape in one
+ * call (L = 1 for pkv_compress_layer), whatever their budgets k_l.
+ * HOST only, pure.  Returns 0 if the descriptor is invalid or L is not in
+ * 1..1024.
  */
-size_t pkv_workspace_bytes(const pkv_layer_desc* desc);
+size_t pkv_workspace_bytes(const pkv_layer_desc* desc, int32_t L);
 
 /*
  * Compress one layer (Sec. 4.2.2; gather per the appendix "Details of
@@ -135,7 +136,7 @@ size_t pkv_workspace_bytes(const pkv_layer_desc* desc);
  * scores_out DEVICE fp32 [B,Hkv,N] contiguous, or NULL: pooled scores before
  *            selection, defined for i < n_b-alpha when k_l < n_b; other
  *            entries are left untouched.
- * workspace  DEVICE, 256-byte aligned, >= pkv_workspace_bytes(desc) bytes;
+ * workspace  DEVICE, 256-byte aligned, >= pkv_workspace_bytes(desc, 1) bytes;
  *            contents on entry are irrelevant, contents on exit undefined.
  *            Concurrent calls must use distinct workspaces.
  * stream     hipStream_t.
@@ -162,9 +163,9 @@ int pkv_compress_layer(const pkv_layer_desc* desc, const void* Q_win,
  *            HOST arrays of L DEVICE pointers, each as in
  *            pkv_compress_layer (scores_out may be NULL, or hold NULLs).
  * seq_lens   DEVICE int32[B] or NULL; shared by all layers.
- * workspace  DEVICE, >= pkv_workspace_bytes(&descs[0]) bytes.
- * Errors: as pkv_compress_layer; additionally L < 1 or differing layer
- * shapes -> PKV_ERR_INVALID_ARG.
+ * workspace  DEVICE, >= pkv_workspace_bytes(&descs[0], L) bytes.
+ * Errors: as pkv_compress_layer; additionally L outside 1..1024 or differing
+ * layer shapes -> PKV_ERR_INVALID_ARG.
  */
 int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs,
                         const void* const* Q_win, const void* const* K,
@@ -195,7 +196,8 @@ typedef enum {
   PKV_KERNEL_SCORE_FINALIZE = 1,
   PKV_KERNEL_SCORE_ACCUM = 2, /* sweep 2 over K: per-key window scores      */
   PKV_KERNEL_POOL_SELECT = 3,
-  PKV_KERNEL_GATHER = 4
+  PKV_KERNEL_GATHER = 4,
+  PKV_KERNEL_SCORE_RESIDENT = 5 /* both sweeps, K held in registers (all layers) */
 } pkv_kernel_id;
 
 int pkv_compress_layers_profiled(

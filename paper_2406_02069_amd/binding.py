@@ -49,7 +49,7 @@ def load() -> ctypes.CDLL:
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
         lib.pkv_budgets.argtypes = [i32, i32, i32, i32, vp]
         lib.pkv_budgets.restype = ctypes.c_int
-        lib.pkv_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc)]
+        lib.pkv_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc), i32]
         lib.pkv_workspace_bytes.restype = ctypes.c_size_t
         lib.pkv_compress_layer.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 10 + [ctypes.c_size_t, vp]
         lib.pkv_compress_layer.restype = ctypes.c_int
@@ -93,12 +93,12 @@ def make_desc(Q_win: torch.Tensor, K: torch.Tensor, k_l: int, pool: int, pool_w:
                      K.stride(0), K.stride(1), K.stride(2), o[0], o[1], o[2])
 
 
-def workspace_bytes(desc: LayerDesc) -> int:
-    return int(load().pkv_workspace_bytes(ctypes.byref(desc)))
+def workspace_bytes(desc: LayerDesc, L: int = 1) -> int:
+    return int(load().pkv_workspace_bytes(ctypes.byref(desc), L))
 
 
-def alloc_workspace(desc: LayerDesc, device) -> torch.Tensor:
-    nbytes = workspace_bytes(desc)
+def alloc_workspace(desc: LayerDesc, device, L: int = 1) -> torch.Tensor:
+    nbytes = workspace_bytes(desc, L)
     if nbytes == 0:
         raise PkvError(ERR_INVALID_ARG, "pkv_workspace_bytes")
     return torch.empty(nbytes, dtype=torch.uint8, device=device)  # torch allocations are >= 256-byte aligned
@@ -161,7 +161,7 @@ class LayersCall:
         self.outputs = [alloc_outputs(Q_win[l], K[l], k_ls[l], want_scores) for l in range(L)]
         self.descs = (LayerDesc * L)(*[make_desc(Q_win[l], K[l], k_ls[l], pool, pool_w, self.outputs[l][0])
                                         for l in range(L)])
-        self.workspace = alloc_workspace(self.descs[0], K[0].device)
+        self.workspace = alloc_workspace(self.descs[0], K[0].device, L)
         arr = ctypes.c_void_p * L
 
         def ptrs(ts):
@@ -185,7 +185,7 @@ def compress_layers(Q_win, K, V, k_ls, pool, pool_w, seq_lens=None, want_scores=
     return LayersCall(Q_win, K, V, k_ls, pool, pool_w, seq_lens, want_scores).run()
 
 
-KERNEL_NAMES = ["score_stats", "score_finalize", "score_accum", "pool_select", "gather"]
+KERNEL_NAMES = ["score_stats", "score_finalize", "score_accum", "pool_select", "gather", "score_resident"]
 
 
 class HipEvents:

@@ -1,7 +1,8 @@
 // Host side of libpkv: budget allocation (Sec. 4.2.1), argument validation, workspace carve-up and
-// the launch sequence of one layer (Sec. 4.2.2 + gather).  Nothing here touches device memory.
+// the launch sequence (Sec. 4.2.2 + gather).  Nothing here touches device memory.
 #include <math.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include "pkv_internal.h"
 
@@ -9,35 +10,51 @@ namespace pkv {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-Plan make_plan(const pkv_layer_desc& d) {
+// How a call is split over the device.  Derived from the shape and the layer count only (never from
+// k_l), so that one workspace size serves every budget.
+Plan make_plan(const pkv_layer_desc& d, int L) {
   Plan p;
+  memset(&p, 0, sizeof(p));
   p.G = d.Hq / d.Hkv;
   p.R = p.G * d.alpha;
+  p.BH = d.B * d.Hkv;
+  p.L = L;
+  // --- register-resident path ---
+  p.res_Rpad = (p.R + 127) / 128 * 128;
+  p.res_nrb = p.res_Rpad / 128;
+  p.TPU = (d.N + kResidentKeys - 1) / kResidentKeys;
+  p.resident_ok = p.res_Rpad <= kResidentMaxRows && p.TPU <= kResidentGrid;
+  p.UPR = p.resident_ok ? kResidentGrid / p.TPU : 1;
+  // --- per-layer streaming path ---
   p.RT = p.R <= 32 ? 1 : (p.R <= 64 ? 2 : 4);
   p.RB = 32 * p.RT;
   p.nrb = (p.R + p.RB - 1) / p.RB;
   p.Rpad = p.nrb * p.RB;
-  p.BH = d.B * d.Hkv;
-  // Aim at ~4 workgroups per compute unit (256 CUs) while keeping at least one tile per wave.
   const long long keys_total = (long long)p.BH * p.nrb * d.N;
-  long long kc = (keys_total / 1024 + 127) / 128 * 128;
+  long long kc = (keys_total / 1024 + 127) / 128 * 128;  // ~4 workgroups per compute unit
   if (kc < 128) kc = 128;
   if (kc > 1024) kc = 1024;
-  if (const char* e = getenv("PKV_KC")) {  // tuning knob for experiments; multiple of 128
-    const long long v = atoll(e);
-    if (v >= 128 && v % 128 == 0) kc = v;
-  }
   p.KC = (int)kc;
   p.nchunk = (d.N + p.KC - 1) / p.KC;
+  // --- workspace: large enough for either path ---
+  const size_t U = (size_t)L * p.BH;
+  const size_t part_res = p.resident_ok ? U * p.TPU * p.res_Rpad * sizeof(float2) : 0;
+  const size_t part_str = (size_t)p.BH * p.Rpad * p.nchunk * sizeof(float2);
+  const size_t raw_res = U * d.N * sizeof(float);
+  const size_t raw_str = U * p.nrb * d.N * sizeof(float);
   size_t off = 0;
+  p.off_cnt = off;
+  off += align256((U + 1) * sizeof(int32_t));
   p.off_part = off;
-  off += align256((size_t)p.BH * p.Rpad * p.nchunk * sizeof(float2));
+  off += align256(part_res > part_str ? part_res : part_str);
   p.off_cfin = off;
   off += align256((size_t)p.BH * p.Rpad * sizeof(float));
   p.off_raw = off;
-  off += align256((size_t)p.nrb * p.BH * d.N * sizeof(float));
+  off += align256(raw_res > raw_str ? raw_res : raw_str);
   p.off_pooled = off;
-  off += align256((size_t)p.BH * d.N * sizeof(float));
+  off += align256(U * d.N * sizeof(float));
+  p.off_dbg = off;
+  off += align256((size_t)kResidentGrid * 8 * sizeof(long long));
   p.total = off;
   return p;
 }
@@ -91,74 +108,180 @@ struct Recorder {
   int32_t n_events;
   int32_t* kernel_ids;
   int32_t used;
-  bool overflow;
   void begin(hipStream_t s) {
     used = 0;
-    overflow = n_events < 1;
-    if (!overflow) hipEventRecord(static_cast<hipEvent_t>(events[used++]), s);
+    (void)hipEventRecord(static_cast<hipEvent_t>(events[used++]), s);
   }
   void after(int id, hipStream_t s) {
-    if (used >= n_events) {
-      overflow = true;
-      return;
-    }
+    if (used >= n_events) return;
     kernel_ids[used - 1] = id;
-    hipEventRecord(static_cast<hipEvent_t>(events[used++]), s);
+    (void)hipEventRecord(static_cast<hipEvent_t>(events[used++]), s);
   }
 };
 
-// Queue the kernels of one layer.  All arguments have been validated.
-static int run_layer(const pkv_layer_desc& d, const Plan& plan, const LayerPtrs& p, const int32_t* seq_lens,
-                     void* workspace, hipStream_t stream, Recorder* rec = nullptr) {
-  char* ws = static_cast<char*>(workspace);
-  ScoreArgs sa;
-  sa.Q = static_cast<const uint16_t*>(p.Q);
-  sa.K = static_cast<const uint16_t*>(p.K);
-  sa.seq_lens = seq_lens;
-  sa.part = reinterpret_cast<float2*>(ws + plan.off_part);
-  sa.cfin = reinterpret_cast<float*>(ws + plan.off_cfin);
-  sa.raw = reinterpret_cast<float*>(ws + plan.off_raw);
-  sa.B = d.B; sa.Hq = d.Hq; sa.Hkv = d.Hkv; sa.G = plan.G; sa.alpha = d.alpha; sa.N = d.N; sa.k_l = d.k_l;
-  sa.R = plan.R; sa.Rpad = plan.Rpad; sa.nrb = plan.nrb; sa.KC = plan.KC; sa.nchunk = plan.nchunk;
-  sa.RT = plan.RT; sa.d = d.d;
-  sa.q_sb = d.q_sb; sa.q_sh = d.q_sh; sa.q_st = d.q_st;
-  sa.kv_sb = d.kv_sb; sa.kv_sh = d.kv_sh; sa.kv_st = d.kv_st;
-  sa.kappa = (float)(1.4426950408889634 / sqrt((double)d.d));
-
-  const int k_cap = d.k_l < d.N ? d.k_l : d.N;
-  SelectArgs se;
-  se.raw = sa.raw;
-  se.pooled = p.scores_out ? p.scores_out : reinterpret_cast<float*>(ws + plan.off_pooled);
-  se.seq_lens = seq_lens;
-  se.idx_out = p.idx_out;
-  se.count_out = p.count_out;
-  se.B = d.B; se.Hkv = d.Hkv; se.N = d.N; se.alpha = d.alpha; se.k_l = d.k_l; se.k_cap = k_cap;
-  se.nrb = plan.nrb; se.pool = (d.pool_w == 1) ? PKV_POOL_NONE : d.pool; se.pool_w = d.pool_w;
-  se.inv_G = 1.0f / (float)plan.G;
-
-  GatherArgs ga;
-  ga.K = sa.K;
-  ga.V = static_cast<const uint16_t*>(p.V);
-  ga.K_out = static_cast<uint16_t*>(p.K_out);
-  ga.V_out = static_cast<uint16_t*>(p.V_out);
-  ga.idx = p.idx_out;
-  ga.B = d.B; ga.Hkv = d.Hkv; ga.k_cap = k_cap; ga.d = d.d;
-  ga.kv_sb = d.kv_sb; ga.kv_sh = d.kv_sh; ga.kv_st = d.kv_st;
-  ga.o_sb = d.o_sb; ga.o_sh = d.o_sh; ga.o_st = d.o_st;
-
-  if (d.k_l < d.N) {  // otherwise every sequence keeps everything and no score is needed
-    if (launch_score_stats(sa, stream) != hipSuccess) return PKV_ERR_HIP;
-    if (rec) rec->after(PKV_KERNEL_SCORE_STATS, stream);
-    if (launch_score_finalize(sa, stream) != hipSuccess) return PKV_ERR_HIP;
-    if (rec) rec->after(PKV_KERNEL_SCORE_FINALIZE, stream);
-    if (launch_score_accum(sa, stream) != hipSuccess) return PKV_ERR_HIP;
-    if (rec) rec->after(PKV_KERNEL_SCORE_ACCUM, stream);
+// The register-resident kernel needs one co-resident workgroup on each of 256 compute units.
+static bool device_fits_resident() {
+  static int cached[64];  // 0 unknown, 1 yes, 2 no
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+  if (cached[dev] == 0) {
+    int cus = 0;
+    const hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    cached[dev] = (e == hipSuccess && cus >= kResidentGrid) ? 1 : 2;
   }
-  if (launch_pool_select(se, stream) != hipSuccess) return PKV_ERR_HIP;
-  if (rec) rec->after(PKV_KERNEL_POOL_SELECT, stream);
-  if (launch_gather(ga, stream) != hipSuccess) return PKV_ERR_HIP;
-  if (rec) rec->after(PKV_KERNEL_GATHER, stream);
+  return cached[dev] == 1;
+}
+
+static bool use_resident(const Plan& plan) {
+  if (const char* e = getenv("PKV_SCORE_PATH")) {  // test hook: "stream" forces the per-layer kernels
+    if (!strcmp(e, "stream")) return false;
+  }
+  return plan.resident_ok && device_fits_resident();
+}
+
+// Queue the kernels of L layers.  All arguments have been validated.
+static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, const LayerPtrs* ptrs,
+                      const int32_t* seq_lens, void* workspace, hipStream_t stream, Recorder* rec) {
+  const pkv_layer_desc& d = descs[0];
+  char* ws = static_cast<char*>(workspace);
+  float* raw = reinterpret_cast<float*>(ws + plan.off_raw);
+  float* pooled_ws = reinterpret_cast<float*>(ws + plan.off_pooled);
+  const float kappa = (float)(1.4426950408889634 / sqrt((double)d.d));
+  const bool resident = use_resident(plan);
+  bool any_scores = false;
+  for (int32_t l = 0; l < L; ++l) any_scores = any_scores || descs[l].k_l < d.N;
+  if (rec) rec->begin(stream);
+
+  // ---- scoring: un-pooled group-mean scores of every prefix key -> raw ----
+  if (any_scores && resident) {
+    for (int32_t l0 = 0; l0 < L; l0 += kResidentMaxLayers) {
+      const int32_t nl = L - l0 < kResidentMaxLayers ? L - l0 : kResidentMaxLayers;
+      ResidentArgs ra;
+      memset(&ra, 0, sizeof(ra));
+      for (int32_t i = 0; i < nl; ++i) {
+        ra.layer[i].Q = static_cast<const uint16_t*>(ptrs[l0 + i].Q);
+        ra.layer[i].K = static_cast<const uint16_t*>(ptrs[l0 + i].K);
+        ra.layer[i].k_l = descs[l0 + i].k_l;
+      }
+      ra.seq_lens = seq_lens;
+      ra.U = nl * plan.BH;
+      ra.raw = raw + (size_t)l0 * plan.BH * d.N;
+      ra.part = reinterpret_cast<float2*>(ws + plan.off_part);
+      ra.cnt = reinterpret_cast<int32_t*>(ws + plan.off_cnt);
+      ra.err = ra.cnt + ra.U;
+      ra.dbg = reinterpret_cast<long long*>(ws + plan.off_dbg);
+      ra.L = nl; ra.B = d.B; ra.Hq = d.Hq; ra.Hkv = d.Hkv; ra.G = plan.G; ra.alpha = d.alpha; ra.N = d.N;
+      ra.R = plan.R; ra.Rpad = plan.res_Rpad; ra.nrb = plan.res_nrb; ra.TPU = plan.TPU; ra.UPR = plan.UPR;
+      ra.nrounds = (ra.U + plan.UPR - 1) / plan.UPR;
+      ra.d = d.d;
+      ra.q_sb = d.q_sb; ra.q_sh = d.q_sh; ra.q_st = d.q_st;
+      ra.kv_sb = d.kv_sb; ra.kv_sh = d.kv_sh; ra.kv_st = d.kv_st;
+      ra.kappa = kappa;
+      ra.inv_G = 1.0f / (float)plan.G;
+      if (launch_score_resident(ra, stream) != hipSuccess) return PKV_ERR_HIP;
+      if (rec) rec->after(PKV_KERNEL_SCORE_RESIDENT, stream);
+    }
+  } else if (any_scores) {
+    for (int32_t l = 0; l < L; ++l) {
+      if (descs[l].k_l >= d.N) continue;
+      ScoreArgs sa;
+      sa.Q = static_cast<const uint16_t*>(ptrs[l].Q);
+      sa.K = static_cast<const uint16_t*>(ptrs[l].K);
+      sa.seq_lens = seq_lens;
+      sa.part = reinterpret_cast<float2*>(ws + plan.off_part);
+      sa.cfin = reinterpret_cast<float*>(ws + plan.off_cfin);
+      sa.raw = raw + (size_t)l * plan.nrb * plan.BH * d.N;
+      sa.B = d.B; sa.Hq = d.Hq; sa.Hkv = d.Hkv; sa.G = plan.G; sa.alpha = d.alpha; sa.N = d.N;
+      sa.k_l = descs[l].k_l;
+      sa.R = plan.R; sa.Rpad = plan.Rpad; sa.nrb = plan.nrb; sa.KC = plan.KC; sa.nchunk = plan.nchunk;
+      sa.RT = plan.RT; sa.d = d.d;
+      sa.q_sb = d.q_sb; sa.q_sh = d.q_sh; sa.q_st = d.q_st;
+      sa.kv_sb = d.kv_sb; sa.kv_sh = d.kv_sh; sa.kv_st = d.kv_st;
+      sa.kappa = kappa;
+      if (launch_score_stats(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+      if (rec) rec->after(PKV_KERNEL_SCORE_STATS, stream);
+      if (launch_score_finalize(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+      if (rec) rec->after(PKV_KERNEL_SCORE_FINALIZE, stream);
+      if (launch_score_accum(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+      if (rec) rec->after(PKV_KERNEL_SCORE_ACCUM, stream);
+    }
+  }
+
+  // ---- pooling + per-head top-k, then gather; all layers per launch ----
+  for (int32_t l0 = 0; l0 < L; l0 += kBatchMaxLayers) {
+    const int32_t nl = L - l0 < kBatchMaxLayers ? L - l0 : kBatchMaxLayers;
+    SelectBatchArgs se;
+    GatherBatchArgs ga;
+    memset(&se, 0, sizeof(se));
+    memset(&ga, 0, sizeof(ga));
+    int32_t k_cap_max = 0;
+    for (int32_t i = 0; i < nl; ++i) {
+      const int32_t l = l0 + i;
+      const int32_t k_cap = descs[l].k_l < d.N ? descs[l].k_l : d.N;
+      k_cap_max = k_cap > k_cap_max ? k_cap : k_cap_max;
+      se.layer[i].pooled = ptrs[l].scores_out ? ptrs[l].scores_out : pooled_ws + (size_t)l * plan.BH * d.N;
+      se.layer[i].idx_out = ptrs[l].idx_out;
+      se.layer[i].count_out = ptrs[l].count_out;
+      se.layer[i].k_l = descs[l].k_l;
+      se.layer[i].k_cap = k_cap;
+      se.layer[i].write_pooled = ptrs[l].scores_out ? 1 : 0;
+      ga.layer[i].K = static_cast<const uint16_t*>(ptrs[l].K);
+      ga.layer[i].V = static_cast<const uint16_t*>(ptrs[l].V);
+      ga.layer[i].K_out = static_cast<uint16_t*>(ptrs[l].K_out);
+      ga.layer[i].V_out = static_cast<uint16_t*>(ptrs[l].V_out);
+      ga.layer[i].idx = ptrs[l].idx_out;
+      ga.layer[i].o_sb = descs[l].o_sb; ga.layer[i].o_sh = descs[l].o_sh; ga.layer[i].o_st = descs[l].o_st;
+      ga.layer[i].k_cap = k_cap;
+    }
+    const int nrb = resident ? 1 : plan.nrb;
+    se.raw = raw + (size_t)l0 * nrb * plan.BH * d.N;
+    se.seq_lens = seq_lens;
+    se.B = d.B; se.Hkv = d.Hkv; se.N = d.N; se.alpha = d.alpha;
+    se.pool = (d.pool_w == 1) ? PKV_POOL_NONE : d.pool;
+    se.pool_w = d.pool_w;
+    se.nrb = nrb;
+    se.inv_G = resident ? 1.0f : 1.0f / (float)plan.G;
+    ga.L = nl; ga.B = d.B; ga.Hkv = d.Hkv; ga.d = d.d; ga.k_cap_max = k_cap_max;
+    ga.kv_sb = d.kv_sb; ga.kv_sh = d.kv_sh; ga.kv_st = d.kv_st;
+    if (launch_pool_select_batch(se, nl, stream) != hipSuccess) return PKV_ERR_HIP;
+    if (rec) rec->after(PKV_KERNEL_POOL_SELECT, stream);
+    if (launch_gather_batch(ga, stream) != hipSuccess) return PKV_ERR_HIP;
+    if (rec) rec->after(PKV_KERNEL_GATHER, stream);
+  }
   return PKV_OK;
+}
+
+static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
+                                const void* const* K, const void* const* V, const int32_t* seq_lens,
+                                void* const* K_out, void* const* V_out, int32_t* const* idx_out,
+                                int32_t* const* count_out, float* const* scores_out, void* workspace,
+                                size_t workspace_bytes, void* stream, Recorder* rec) {
+  if (L < 1 || L > kMaxLayers || !descs || !Q_win || !K || !V || !K_out || !V_out || !idx_out || !count_out)
+    return PKV_ERR_INVALID_ARG;
+  if ((uintptr_t)seq_lens & 3) return PKV_ERR_INVALID_ARG;
+  LayerPtrs ptrs[kMaxLayers];
+  for (int32_t l = 0; l < L; ++l) {
+    int rc = check_desc(&descs[l]);
+    if (rc != PKV_OK) return rc;
+    const pkv_layer_desc &a = descs[0], &b = descs[l];
+    if (a.B != b.B || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.N != b.N || a.alpha != b.alpha ||
+        a.pool != b.pool || a.pool_w != b.pool_w || a.q_sb != b.q_sb || a.q_sh != b.q_sh || a.q_st != b.q_st ||
+        a.kv_sb != b.kv_sb || a.kv_sh != b.kv_sh || a.kv_st != b.kv_st)
+      return PKV_ERR_INVALID_ARG;
+    ptrs[l] = {Q_win[l], K[l], V[l], K_out[l], V_out[l], idx_out[l], count_out[l],
+               scores_out ? scores_out[l] : nullptr};
+    rc = check_ptrs(ptrs[l]);
+    if (rc != PKV_OK) return rc;
+  }
+  const Plan plan = make_plan(descs[0], L);
+  const int rc = check_workspace(plan, workspace, workspace_bytes);
+  if (rc != PKV_OK) return rc;
+  if (rec) {
+    if (!rec->events || !rec->kernel_ids || rec->n_events < 5 * L + 1) return PKV_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < 5 * L + 1; ++i)
+      if (!rec->events[i]) return PKV_ERR_INVALID_ARG;
+  }
+  return run_layers(L, descs, plan, ptrs, seq_lens, workspace, static_cast<hipStream_t>(stream), rec);
 }
 
 }  // namespace pkv
@@ -203,62 +326,17 @@ int pkv_budgets(int32_t L, int32_t avg_budget, int32_t beta, int32_t alpha, int3
   return PKV_OK;
 }
 
-size_t pkv_workspace_bytes(const pkv_layer_desc* desc) {
-  if (check_desc(desc) != PKV_OK) return 0;
-  return make_plan(*desc).total;
+size_t pkv_workspace_bytes(const pkv_layer_desc* desc, int32_t L) {
+  if (L < 1 || L > kMaxLayers || check_desc(desc) != PKV_OK) return 0;
+  return make_plan(*desc, L).total;
 }
 
 int pkv_compress_layer(const pkv_layer_desc* desc, const void* Q_win, const void* K, const void* V,
                        const int32_t* seq_lens, void* K_out, void* V_out, int32_t* idx_out, int32_t* count_out,
                        float* scores_out, void* workspace, size_t workspace_bytes, void* stream) {
-  int rc = check_desc(desc);
-  if (rc != PKV_OK) return rc;
-  const LayerPtrs p = {Q_win, K, V, K_out, V_out, idx_out, count_out, scores_out};
-  rc = check_ptrs(p);
-  if (rc != PKV_OK) return rc;
-  if ((uintptr_t)seq_lens & 3) return PKV_ERR_INVALID_ARG;
-  const Plan plan = make_plan(*desc);
-  rc = check_workspace(plan, workspace, workspace_bytes);
-  if (rc != PKV_OK) return rc;
-  return run_layer(*desc, plan, p, seq_lens, workspace, static_cast<hipStream_t>(stream));
-}
-
-static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
-                                const void* const* K, const void* const* V, const int32_t* seq_lens,
-                                void* const* K_out, void* const* V_out, int32_t* const* idx_out,
-                                int32_t* const* count_out, float* const* scores_out, void* workspace,
-                                size_t workspace_bytes, void* stream, Recorder* rec) {
-  if (L < 1 || !descs || !Q_win || !K || !V || !K_out || !V_out || !idx_out || !count_out) return PKV_ERR_INVALID_ARG;
-  if ((uintptr_t)seq_lens & 3) return PKV_ERR_INVALID_ARG;
-  for (int32_t l = 0; l < L; ++l) {
-    int rc = check_desc(&descs[l]);
-    if (rc != PKV_OK) return rc;
-    const pkv_layer_desc &a = descs[0], &b = descs[l];
-    if (a.B != b.B || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.N != b.N || a.alpha != b.alpha ||
-        a.pool != b.pool || a.pool_w != b.pool_w || a.q_sb != b.q_sb || a.q_sh != b.q_sh || a.q_st != b.q_st ||
-        a.kv_sb != b.kv_sb || a.kv_sh != b.kv_sh || a.kv_st != b.kv_st)
-      return PKV_ERR_INVALID_ARG;
-    const LayerPtrs p = {Q_win[l], K[l], V[l], K_out[l], V_out[l], idx_out[l], count_out[l],
-                         scores_out ? scores_out[l] : nullptr};
-    rc = check_ptrs(p);
-    if (rc != PKV_OK) return rc;
-  }
-  const Plan plan = make_plan(descs[0]);
-  int rc = check_workspace(plan, workspace, workspace_bytes);
-  if (rc != PKV_OK) return rc;
-  if (rec) {
-    if (!rec->events || !rec->kernel_ids || rec->n_events < 5 * L + 1) return PKV_ERR_INVALID_ARG;
-    for (int32_t i = 0; i < 5 * L + 1; ++i)
-      if (!rec->events[i]) return PKV_ERR_INVALID_ARG;
-    rec->begin(static_cast<hipStream_t>(stream));
-  }
-  for (int32_t l = 0; l < L; ++l) {
-    const LayerPtrs p = {Q_win[l], K[l], V[l], K_out[l], V_out[l], idx_out[l], count_out[l],
-                         scores_out ? scores_out[l] : nullptr};
-    rc = run_layer(descs[l], plan, p, seq_lens, workspace, static_cast<hipStream_t>(stream), rec);
-    if (rc != PKV_OK) return rc;
-  }
-  return PKV_OK;
+  float* const* so = scores_out ? &scores_out : nullptr;
+  return compress_layers_impl(1, desc, &Q_win, &K, &V, seq_lens, &K_out, &V_out, &idx_out, &count_out, so,
+                              workspace, workspace_bytes, stream, nullptr);
 }
 
 int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win, const void* const* K,
@@ -276,7 +354,7 @@ int pkv_compress_layers_profiled(int32_t L, const pkv_layer_desc* descs, const v
                                  size_t workspace_bytes, void* stream, void* const* events, int32_t n_events,
                                  int32_t* kernel_ids, int32_t* n_used) {
   if (!n_used) return PKV_ERR_INVALID_ARG;
-  Recorder rec = {events, n_events, kernel_ids, 0, false};
+  Recorder rec = {events, n_events, kernel_ids, 0};
   const int rc = compress_layers_impl(L, descs, Q_win, K, V, seq_lens, K_out, V_out, idx_out, count_out,
                                       scores_out, workspace, workspace_bytes, stream, &rec);
   *n_used = rec.used;

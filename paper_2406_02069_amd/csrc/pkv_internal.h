@@ -16,23 +16,32 @@ constexpr int kKeysPerTile = 32;     // one MFMA tile of keys
 constexpr int kWavesPerBlock = 4;    // score kernels
 constexpr int kSelectThreads = 1024; // pool + select kernel
 
-// How one layer call is split over the device; derived from the shape only (never from k_l), so
-// that one workspace serves every layer of a model.
+constexpr int kMaxLayers = 1024;     // layers per call
+
+// How a call is split over the device; derived from the shape and the layer count only (never from
+// k_l), so that one workspace size serves every budget.
 struct Plan {
   int G;         // query heads per KV head
   int R;         // query rows sharing one KV head: G * alpha
+  int BH;        // B * Hkv
+  int L;
+  // register-resident scoring
+  bool resident_ok;
+  int res_Rpad, res_nrb;  // rows padded to 128-row blocks
+  int TPU;       // 1024-key parts per unit
+  int UPR;       // units per round of 256 workgroups
+  // per-layer streaming scoring
   int RT;        // 32-row MFMA tiles per row block (1, 2 or 4)
   int RB;        // rows per row block: 32 * RT
   int nrb;       // row blocks: ceil(R / RB)
   int Rpad;      // nrb * RB
   int KC;        // keys per score workgroup (multiple of 128)
   int nchunk;    // ceil(N / KC)
-  int BH;        // B * Hkv
   // workspace carve-up (byte offsets, each 256-aligned)
-  size_t off_part, off_cfin, off_raw, off_pooled, total;
+  size_t off_cnt, off_part, off_cfin, off_raw, off_pooled, off_dbg, total;
 };
 
-Plan make_plan(const pkv_layer_desc& d);
+Plan make_plan(const pkv_layer_desc& d, int L);
 
 struct ScoreArgs {
   const uint16_t* Q;
@@ -46,31 +55,77 @@ struct ScoreArgs {
   float kappa;   // log2(e) / sqrt(d)
 };
 
-struct SelectArgs {
-  const float* raw;       // [nrb][BH][N]
-  float* pooled;          // [BH][N]: scores_out if the caller wants it, else workspace
-  const int32_t* seq_lens;
-  int32_t* idx_out;       // [BH][k_cap]
-  int32_t* count_out;     // [B]
-  int32_t B, Hkv, N, alpha, k_l, k_cap, nrb, pool, pool_w;
-  float inv_G;
+
+// ---- register-resident scoring over many layers (pkv_resident.hip) ----
+constexpr int kResidentGrid = 256;      // persistent workgroups, one per compute unit
+constexpr int kResidentKeys = 1024;     // keys held in registers by one workgroup
+constexpr int kResidentMaxRows = 1024;  // G * alpha (padded to 128) the LDS normaliser table can hold
+constexpr int kResidentMaxLayers = 96;  // per launch (kernel-argument table)
+
+struct ResidentLayer {
+  const uint16_t* Q;
+  const uint16_t* K;
+  int32_t k_l;
+  int32_t pad;
 };
 
-struct GatherArgs {
+struct ResidentArgs {
+  ResidentLayer layer[kResidentMaxLayers];
+  const int32_t* seq_lens;
+  float* raw;     // [L][BH][N] un-pooled scores
+  float2* part;   // [U][TPU][Rpad] per-part softmax statistics (log2 domain)
+  int32_t* cnt;   // [U] arrivals per unit; zeroed by the launcher
+  int32_t* err;   // == cnt + U: set to 1 if a bounded wait gave up
+  long long* dbg; // per-workgroup phase timers (development builds only), may be null
+  int32_t L, B, Hq, Hkv, G, alpha, N, R, Rpad, nrb, TPU, UPR, U, nrounds, d;
+  int64_t q_sb, q_sh, q_st, kv_sb, kv_sh, kv_st;
+  float kappa, inv_G;
+};
+
+// ---- pooling + selection and gather over many layers ----
+constexpr int kBatchMaxLayers = 40;  // per launch (kernel-argument table)
+
+struct SelectLayer {
+  float* pooled;       // [BH][N]: scores_out of the layer, else workspace
+  int32_t* idx_out;    // [BH][k_cap]
+  int32_t* count_out;  // [B]
+  int32_t k_l, k_cap;
+  int32_t write_pooled;  // the caller asked for scores_out
+  int32_t pad;
+};
+
+struct SelectBatchArgs {
+  SelectLayer layer[kBatchMaxLayers];
+  const float* raw;    // [L][nrb][BH][N], first layer of this launch
+  const int32_t* seq_lens;
+  int32_t B, Hkv, N, alpha, pool, pool_w;
+  int32_t nrb;         // partial score arrays to add per layer
+  float inv_G;         // factor applied to the sum of the partials
+};
+
+struct GatherLayer {
   const uint16_t* K;
   const uint16_t* V;
   uint16_t* K_out;
   uint16_t* V_out;
-  const int32_t* idx;     // [BH][k_cap]
-  int32_t B, Hkv, k_cap, d;
-  int64_t kv_sb, kv_sh, kv_st, o_sb, o_sh, o_st;
+  const int32_t* idx;
+  int64_t o_sb, o_sh, o_st;
+  int32_t k_cap, pad;
 };
+
+struct GatherBatchArgs {
+  GatherLayer layer[kBatchMaxLayers];
+  int32_t L, B, Hkv, d, k_cap_max;
+  int64_t kv_sb, kv_sh, kv_st;
+};
+
+hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s);
+hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipStream_t s);
+hipError_t launch_gather_batch(const GatherBatchArgs& a, hipStream_t s);
 
 // Each returns hipSuccess or the launch error.
 hipError_t launch_score_stats(const ScoreArgs& a, hipStream_t s);
 hipError_t launch_score_finalize(const ScoreArgs& a, hipStream_t s);
 hipError_t launch_score_accum(const ScoreArgs& a, hipStream_t s);
-hipError_t launch_pool_select(const SelectArgs& a, hipStream_t s);
-hipError_t launch_gather(const GatherArgs& a, hipStream_t s);
 
 }  // namespace pkv

@@ -24,11 +24,13 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// 16 bytes as a native vector (HIP's uint4 class keeps such values out of registers when staged in arrays)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
-__device__ __forceinline__ bf16x8 as_frag(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+__device__ __forceinline__ bf16x8 as_frag(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
 // Position of 16-byte segment `seg` of tile row `row` inside an LDS tile with SEG segments per row.
 // The XOR spreads the 16 rows that one ds_read_b128 phase touches over 16 different bank groups.
@@ -61,13 +63,13 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
   constexpr int NLD = SEG / 2; // global loads per lane per 32-key tile
   constexpr int TILE_U4 = 32 * SEG;
   constexpr int LDS_U4 = (RB * SEG > kWavesPerBlock * TILE_U4) ? RB * SEG : kWavesPerBlock * TILE_U4;
-  __shared__ uint4 lds[LDS_U4];
+  __shared__ u32x4 lds[LDS_U4];
   __shared__ float2 red[kWavesPerBlock][RB];
   __shared__ float cst[RB];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps addressing in scalar registers
   const int idx32 = lane & 31;
   const int half = lane >> 5;
 
@@ -102,11 +104,11 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
   for (int e = tid; e < RB * SEG; e += 256) {
     const int row = e / SEG, seg = e - row * SEG;
     const int r = row0 + row;
-    uint4 v = make_uint4(0, 0, 0, 0);
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
     if (r < a.R) {
       const int hh = r / a.alpha, t = r - hh * a.alpha;
       const uint16_t* src = a.Q + (size_t)b * a.q_sb + (size_t)(g * a.G + hh) * a.q_sh + (size_t)t * a.q_st + seg * 8;
-      v = *reinterpret_cast<const uint4*>(src);
+      v = *reinterpret_cast<const u32x4*>(src);
     }
     lds[lds_slot<SEG>(row, seg)] = v;
   }
@@ -133,17 +135,17 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
   __syncthreads();  // Q block consumed; the same LDS now stages K tiles
 
   const uint16_t* Kbase = a.K + (size_t)b * a.kv_sb + (size_t)g * a.kv_sh;
-  uint4* tile = lds + wave * TILE_U4;
+  u32x4* tile = lds + wave * TILE_U4;
   const int kmax = n - 1;
 
-  auto load_tile = [&](int tt, uint4 (&st)[NLD]) {
+  auto load_tile = [&](int tt, u32x4 (&st)[NLD]) {
     const int tile_base = chunk_start + tt * kKeysPerTile;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int e = i * 64 + lane;
       const int row = e / SEG, seg = e - row * SEG;
       const int key = min(tile_base + row, kmax);  // rows at or beyond n are never read
-      st[i] = *reinterpret_cast<const uint4*>(Kbase + (size_t)key * a.kv_st + seg * 8);
+      st[i] = *reinterpret_cast<const u32x4*>(Kbase + (size_t)key * a.kv_st + seg * 8);
     }
   };
 
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ScoreArgs a) {
     limit[j] = (r < a.R) ? npre + (r % a.alpha) : -1;  // last key visible to this query (causal)
   }
 
-  uint4 stage[NLD];
+  u32x4 stage[NLD];
   if (wave < ntiles) load_tile(wave, stage);
 
   for (int tt = wave; tt < ntiles; tt += kWavesPerBlock) {

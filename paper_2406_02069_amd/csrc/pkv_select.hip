@@ -1,15 +1,19 @@
 // Group mean, 1-D pooling and per-head top-k selection (Sec. 4.2.2: "a pooling layer", "the top k^l
 // tokens with the highest scores are selected"; the alpha instruction tokens are always kept).
 //
-// One 1024-thread workgroup per (sequence, KV head):
-//   A. pooled[i] = pool_w-wide max / average of (1/G) * sum over row blocks of raw[i], prefix only;
-//   B. radix select on the fp32 bit patterns (scores are >= 0, so unsigned order = numeric order):
-//      three digit levels (12 + 10 + 10 bits), each a histogram of the keys that match the digits
-//      found so far, followed by a suffix scan that locates the digit holding the kk-th largest key;
-//      the result is the exact threshold T, and how many keys equal to T must be taken;
-//   C. one ordered sweep emits the positions with key > T, and the lowest-position keys == T, in
-//      ascending position order, followed by the window positions.
-// All counters are integers and the sweep is ordered, so the result does not depend on scheduling.
+// One 1024-thread workgroup per unit (layer x sequence x KV head); all layers of a call run in one
+// launch.
+//   A. pooled[i] = pool_w-wide max / average of the un-pooled scores, prefix only, staged tile by tile
+//      through LDS; the fp32 bit patterns become the selection keys (scores are >= 0, so unsigned
+//      order = numeric order).  Keys stay in LDS when the prefix fits (<= 32768 keys), otherwise they
+//      are re-read from the pooled array in global memory.
+//   B. radix select: three digit levels (11 + 11 + 10 bits); each level builds an LDS histogram of the
+//      keys that match the digits found so far and a suffix scan locates the digit holding the kk-th
+//      largest key.  The result is the exact threshold T and how many keys equal to T are needed.
+//   C. ordered emission: every wave owns a contiguous range of positions; ballots give each kept key
+//      its rank, so positions with key > T, and the lowest positions with key == T, come out in
+//      ascending order, followed by the window positions.
+// All counters are integers and the emission is ordered, so the result does not depend on scheduling.
 #include "pkv_internal.h"
 
 namespace pkv {
@@ -17,74 +21,54 @@ namespace {
 
 constexpr int NT = kSelectThreads;
 constexpr int NW = NT / 64;
-constexpr int TS = 4096;  // pooling tile (outputs per iteration)
-constexpr int HIST = 4096;
+constexpr int TS = 2048;           // pooling tile (outputs per iteration)
+constexpr int HIST = 2048;         // bins of the widest digit
+constexpr int kLdsKeys = 32768;    // prefix lengths up to this keep their keys in LDS
 
 // Inclusive scan over the workgroup, thread order.  `scratch` holds NW entries.
-template <typename T>
-__device__ __forceinline__ T block_inclusive_scan(T v, T* scratch, T* total) {
+__device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
-    T u = __shfl_up(v, o);
+    const uint32_t u = __shfl_up(v, o);
     if (lane >= o) v += u;
   }
   __syncthreads();  // scratch may still be read from a previous use
   if (lane == 63) scratch[wave] = v;
   __syncthreads();
-  T base = 0, tot = 0;
+  uint32_t base = 0, tot = 0;
 #pragma unroll
   for (int w = 0; w < NW; ++w) {
-    const T s = scratch[w];
+    const uint32_t s = scratch[w];
     if (w < wave) base += s;
     tot += s;
   }
-  if (total) *total = tot;
+  *total = tot;
   return v + base;
 }
 
-__global__ __launch_bounds__(NT) void pool_select_kernel(const SelectArgs a) {
-  __shared__ float tilebuf[TS + 2 * 32];
-  __shared__ uint32_t hist[HIST];
-  __shared__ unsigned long long scan64[NW];
-  __shared__ uint32_t scan32[NW];
-  __shared__ uint32_t sel_bin, sel_above;
-
+template <bool LDSKEYS>
+__device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb_stride, float inv_G, float* pooled,
+                                            bool write_pooled, int32_t* idx, int npre, int kk, int alpha, int pool,
+                                            int pool_w, uint32_t* lkeys, float* tilebuf, uint32_t* hist,
+                                            uint32_t* scan32, uint32_t* sel) {
   const int tid = threadIdx.x;
-  const int bg = blockIdx.x;
-  const int b = bg / a.Hkv;
-  const int g = bg - b * a.Hkv;
-  int n = a.N;
-  if (a.seq_lens) {
-    n = a.seq_lens[b];
-    n = n < 0 ? 0 : (n > a.N ? a.N : n);
-  }
-  const int count = a.k_l < n ? a.k_l : n;
-  if (g == 0 && tid == 0) a.count_out[b] = count;
-  int32_t* idx = a.idx_out + (size_t)bg * a.k_cap;
+  const int lane = tid & 63, wave = tid >> 6;
+  const uint32_t* gkeys = reinterpret_cast<const uint32_t*>(pooled);
+  auto key_at = [&](int i) -> uint32_t { return LDSKEYS ? lkeys[i] : gkeys[i]; };
 
-  if (a.k_l >= n) {  // keep everything
-    for (int j = tid; j < a.k_cap; j += NT) idx[j] = j < n ? j : -1;
-    return;
-  }
-  const int npre = n - a.alpha;
-  const int kk = a.k_l - a.alpha;  // prefix tokens to select; kk < npre
-  float* pooled = a.pooled + (size_t)bg * a.N;
-
-  // ---- A. group mean + pooling, tile by tile through LDS ----
-  const int r = (a.pool == PKV_POOL_NONE) ? 0 : (a.pool_w - 1) / 2;
-  const bool is_max = a.pool == PKV_POOL_MAX;
-  const float inv_w = 1.0f / (float)a.pool_w;
-  const size_t rb_stride = (size_t)a.B * a.Hkv * a.N;
-  const float* raw = a.raw + (size_t)bg * a.N;
+  // ---- A. group mean + pooling ----
+  const int r = (pool == PKV_POOL_NONE) ? 0 : (pool_w - 1) / 2;
+  const bool is_max = pool == PKV_POOL_MAX;
+  const float inv_w = 1.0f / (float)pool_w;
   for (int t0 = 0; t0 < npre; t0 += TS) {
     for (int e = tid; e < TS + 2 * r; e += NT) {
       const int i = t0 - r + e;
       float v = is_max ? -INFINITY : 0.f;
       if (i >= 0 && i < npre) {
         float s = 0.f;
-        for (int q = 0; q < a.nrb; ++q) s += raw[q * rb_stride + i];
-        v = s * a.inv_G;
+        for (int q = 0; q < nrb; ++q) s += raw[q * rb_stride + i];
+        v = s * inv_G;
       }
       tilebuf[e] = v;
     }
@@ -103,7 +87,8 @@ __global__ __launch_bounds__(NT) void pool_select_kernel(const SelectArgs a) {
           for (int u = 0; u <= 2 * r; ++u) v += tilebuf[e + u];
           v *= inv_w;
         }
-        pooled[i] = v;
+        if (LDSKEYS) lkeys[i] = __float_as_uint(v);
+        if (!LDSKEYS || write_pooled) pooled[i] = v;
       }
     }
     __syncthreads();
@@ -111,81 +96,134 @@ __global__ __launch_bounds__(NT) void pool_select_kernel(const SelectArgs a) {
 
   if (kk > 0) {
     // ---- B. radix select of the kk-th largest key ----
-    const uint32_t* keys = reinterpret_cast<const uint32_t*>(pooled);
     uint32_t prefix = 0, prefix_mask = 0;
     uint32_t remaining = (uint32_t)kk;
-    const int shifts[3] = {20, 10, 0};
-    const int bits[3] = {12, 10, 10};
+    const int shifts[3] = {21, 10, 0};
+    const int bits[3] = {11, 11, 10};
+#pragma unroll
     for (int lvl = 0; lvl < 3; ++lvl) {
       const int shift = shifts[lvl];
       const uint32_t dmask = (1u << bits[lvl]) - 1u;
       for (int e = tid; e < HIST; e += NT) hist[e] = 0;
       __syncthreads();
       for (int i = tid; i < npre; i += NT) {
-        const uint32_t key = keys[i];
+        const uint32_t key = key_at(i);
         if ((key & prefix_mask) == prefix) atomicAdd(&hist[(key >> shift) & dmask], 1u);
       }
       __syncthreads();
-      // thread t owns bins [4t, 4t+4); suffix sum over higher threads
-      const int nbin = 1 << bits[lvl];
-      uint32_t h[4], local = 0;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int bin = 4 * tid + q;
-        h[q] = bin < nbin ? hist[bin] : 0u;
-        local += h[q];
-      }
+      // thread t owns bins 2t, 2t+1; suffix sums over the bins owned by higher threads
+      const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
       uint32_t total;
-      const uint32_t incl = block_inclusive_scan<uint32_t>(local, scan32, &total);
-      uint32_t above = total - incl;  // keys in bins owned by higher threads
-#pragma unroll
-      for (int q = 3; q >= 0; --q) {
-        if (above < remaining && above + h[q] >= remaining) {
-          sel_bin = (uint32_t)(4 * tid + q);
-          sel_above = above;
-        }
-        above += h[q];
+      const uint32_t incl = block_inclusive_scan(h0 + h1, scan32, &total);
+      uint32_t above = total - incl;
+      if (above < remaining && above + h1 >= remaining) {
+        sel[0] = (uint32_t)(2 * tid + 1);
+        sel[1] = above;
+      }
+      above += h1;
+      if (above < remaining && above + h0 >= remaining) {
+        sel[0] = (uint32_t)(2 * tid);
+        sel[1] = above;
       }
       __syncthreads();
-      prefix |= sel_bin << shift;
+      prefix |= sel[0] << shift;
       prefix_mask |= dmask << shift;
-      remaining -= sel_above;
+      remaining -= sel[1];
       __syncthreads();
     }
-    const uint32_t T = prefix;          // bit pattern of the kk-th largest pooled score
-    const uint32_t need_eq = remaining; // keys equal to T to take, lowest positions first (>= 1)
+    const uint32_t T = prefix;           // bit pattern of the kk-th largest pooled score
+    const uint32_t need_eq = remaining;  // keys equal to T to take, lowest positions first (>= 1)
 
     // ---- C. ordered emission ----
-    const int seg = (npre + NT - 1) / NT;
-    const int s0 = min(tid * seg, npre), s1 = min(s0 + seg, npre);
+    const int cw = ((npre + NW - 1) / NW + 63) & ~63;  // positions per wave, multiple of 64
+    const int w0 = min(wave * cw, npre), w1 = min(w0 + cw, npre);
     uint32_t cgt = 0, ceq = 0;
-    for (int i = s0; i < s1; ++i) {
-      const uint32_t key = keys[i];
-      cgt += key > T;
-      ceq += key == T;
+    for (int base = w0; base < w1; base += 64) {
+      const int i = base + lane;
+      const uint32_t key = i < w1 ? key_at(i) : 0u;
+      cgt += __popcll(__ballot(i < w1 && key > T));
+      ceq += __popcll(__ballot(i < w1 && key == T));
     }
-    const unsigned long long packed = ((unsigned long long)cgt << 32) | ceq;
-    const unsigned long long incl = block_inclusive_scan<unsigned long long>(packed, scan64, nullptr);
-    uint32_t gt_before = (uint32_t)(incl >> 32) - cgt;
-    uint32_t eq_before = (uint32_t)(incl & 0xffffffffu) - ceq;
-    for (int i = s0; i < s1; ++i) {
-      const uint32_t key = keys[i];
-      if (key > T) {
-        idx[gt_before + min(eq_before, need_eq)] = i;
-        ++gt_before;
-      } else if (key == T) {
-        if (eq_before < need_eq) idx[gt_before + eq_before] = i;
-        ++eq_before;
-      }
+    __syncthreads();
+    if (lane == 0) {
+      hist[wave] = cgt;
+      hist[NW + wave] = ceq;
+    }
+    __syncthreads();
+    uint32_t gt_before = 0, eq_before = 0;
+    for (int w = 0; w < wave; ++w) {
+      gt_before += hist[w];
+      eq_before += hist[NW + w];
+    }
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int base = w0; base < w1; base += 64) {
+      const int i = base + lane;
+      const uint32_t key = i < w1 ? key_at(i) : 0u;
+      const bool gt = i < w1 && key > T, eq = i < w1 && key == T;
+      const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+      const uint32_t gtb = gt_before + __popcll(bgt & lt_mask);
+      const uint32_t eqb = eq_before + __popcll(beq & lt_mask);
+      if (gt) idx[gtb + min(eqb, need_eq)] = i;
+      if (eq && eqb < need_eq) idx[gtb + eqb] = i;
+      gt_before += __popcll(bgt);
+      eq_before += __popcll(beq);
     }
   }
-  for (int t = tid; t < a.alpha; t += NT) idx[kk + t] = npre + t;
+  for (int t = tid; t < alpha; t += NT) idx[kk + t] = npre + t;
+}
+
+__global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatchArgs a) {
+  extern __shared__ uint32_t lkeys[];  // kLdsKeys entries
+  __shared__ float tilebuf[TS + 2 * 32];
+  __shared__ uint32_t hist[HIST];
+  __shared__ uint32_t scan32[NW];
+  __shared__ uint32_t sel[2];
+
+  const int tid = threadIdx.x;
+  const int BH = a.B * a.Hkv;
+  const int u = blockIdx.x;
+  const int l = u / BH;
+  const int bg = u - l * BH;
+  const int b = bg / a.Hkv;
+  const int g = bg - b * a.Hkv;
+  const SelectLayer& ly = a.layer[l];
+  int n = a.N;
+  if (a.seq_lens) {
+    n = a.seq_lens[b];
+    n = n < 0 ? 0 : (n > a.N ? a.N : n);
+  }
+  const int count = ly.k_l < n ? ly.k_l : n;
+  if (g == 0 && tid == 0) ly.count_out[b] = count;
+  int32_t* idx = ly.idx_out + (size_t)bg * ly.k_cap;
+  if (ly.k_l >= n) {  // keep everything
+    for (int j = tid; j < ly.k_cap; j += NT) idx[j] = j < n ? j : -1;
+    return;
+  }
+  const int npre = n - a.alpha;
+  const int kk = ly.k_l - a.alpha;  // prefix tokens to select; kk < npre
+  const size_t rb_stride = (size_t)BH * a.N;
+  const float* raw = a.raw + ((size_t)l * a.nrb * BH + bg) * a.N;
+  float* pooled = ly.pooled + (size_t)bg * a.N;
+  if (npre <= kLdsKeys)
+    select_unit<true>(raw, a.nrb, rb_stride, a.inv_G, pooled, ly.write_pooled != 0, idx, npre, kk, a.alpha, a.pool,
+                      a.pool_w, lkeys, tilebuf, hist, scan32, sel);
+  else
+    select_unit<false>(raw, a.nrb, rb_stride, a.inv_G, pooled, true, idx, npre, kk, a.alpha, a.pool, a.pool_w,
+                       lkeys, tilebuf, hist, scan32, sel);
 }
 
 }  // namespace
 
-hipError_t launch_pool_select(const SelectArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(pool_select_kernel, dim3(a.B * a.Hkv), dim3(NT), 0, s, a);
+hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipStream_t s) {
+  static bool attr_set = false;
+  const size_t dyn = (size_t)kLdsKeys * sizeof(uint32_t);
+  if (!attr_set) {  // allow 128 KB of dynamic LDS (idempotent; no allocation)
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pool_select_batch_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(pool_select_batch_kernel, dim3(nlayers * a.B * a.Hkv), dim3(NT), dyn, s, a);
   return hipGetLastError();
 }
 

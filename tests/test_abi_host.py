@@ -84,6 +84,8 @@ def test_workspace_size_is_positive_and_budget_independent():
     assert a == b > 0
     assert binding.workspace_bytes(_desc(Hq=30)) == 0        # Hq % Hkv != 0
     assert binding.workspace_bytes(_desc(d=96)) == 0          # unsupported head dim
+    assert binding.workspace_bytes(_desc(), 0) == 0 and binding.workspace_bytes(_desc(), 1025) == 0
+    assert binding.workspace_bytes(_desc(), 32) > a           # grows with the layer count
 
 
 def test_compress_layer_rejects_bad_arguments_before_launching():

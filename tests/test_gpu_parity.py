@@ -11,6 +11,13 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+@pytest.fixture(params=["resident", "stream"])
+def score_path(request, monkeypatch):
+    """Both scoring implementations: K held in registers (default) and the per-layer streaming kernels."""
+    monkeypatch.setenv("PKV_SCORE_PATH", request.param)
+    return request.param
+
+
 def _lens_dev(lens):
     return None if lens is None else torch.from_numpy(np.asarray(lens, dtype=np.int32)).to(DEV)
 
@@ -36,7 +43,7 @@ class _W:  # minimal stand-in for a workload in ad-hoc cases
         self.alpha, self.pool, self.pool_w = alpha, pool, pool_w
 
 
-def test_config0_tiny_mha_all_layers():
+def test_config0_tiny_mha_all_layers(score_path):
     w = synth.WORKLOADS[0]
     ks = binding.budgets(w.L, w.avg_budgets[0], w.beta, w.alpha)
     assert ks == [242, 166, 90, 14]
@@ -47,7 +54,7 @@ def test_config0_tiny_mha_all_layers():
 
 
 @pytest.mark.parametrize("cfg,N", [(1, 1500), (1, 4099), (2, 2500), (4, 1111)])
-def test_scaled_configs_ragged_tiles(cfg, N):
+def test_scaled_configs_ragged_tiles(cfg, N, score_path):
     # several key tiles, several chunks, a ragged tail (N not a multiple of 32), every row-block shape
     w = synth.WORKLOADS[cfg].scaled(N=N, L=3)
     ks = binding.budgets(w.L, w.avg_budgets[0], w.beta, w.alpha)
@@ -56,7 +63,7 @@ def test_scaled_configs_ragged_tiles(cfg, N):
         _run_and_compare(w, layer, ks[layer])
 
 
-def test_config3_scaled_ragged_batch_with_nan_padding():
+def test_config3_scaled_ragged_batch_with_nan_padding(score_path):
     w = synth.WORKLOADS[3].scaled(N=3000, ragged_min=700, B=4)
     ks = binding.budgets(w.L, w.avg_budgets[0], w.beta, w.alpha)
     for layer, k_l in ((0, ks[0]), (1, ks[-1]), (2, 900)):     # 900 > some n_b: those keep everything
@@ -67,14 +74,14 @@ def test_config3_scaled_ragged_batch_with_nan_padding():
 
 @pytest.mark.parametrize("d,Hq,Hkv,alpha", [(64, 8, 8, 8), (64, 16, 2, 8), (64, 12, 4, 5), (128, 4, 4, 1),
                                              (128, 28, 4, 16), (128, 64, 8, 64), (64, 6, 2, 37)])
-def test_head_geometries(d, Hq, Hkv, alpha):
+def test_head_geometries(d, Hq, Hkv, alpha, score_path):
     Q, K, V = _rand(2, Hq, Hkv, d, 777, alpha, seed=d + Hq + alpha)
     for pool, pw in ((synth.POOL_MAX, 7), (synth.POOL_AVG, 5), (synth.POOL_NONE, 1), (synth.POOL_MAX, 63)):
         print("geometry", d, Hq, Hkv, alpha, pool, pw, flush=True)
         _run_and_compare(_W(alpha, pool, pw), 0, alpha + 100, Q, K, V)
 
 
-def test_edge_budgets_and_lengths():
+def test_edge_budgets_and_lengths(score_path):
     alpha = 8
     Q, K, V = _rand(3, 8, 2, 128, 300, alpha, seed=5)
     w = _W(alpha, synth.POOL_MAX, 7)

@@ -44,7 +44,7 @@ Plan make_plan(const pkv_layer_desc& d, int L) {
   const size_t raw_str = U * p.nrb * d.N * sizeof(float);
   size_t off = 0;
   p.off_cnt = off;
-  off += align256((U + 1) * sizeof(int32_t));
+  off += align256((U + 2) * sizeof(int32_t));
   p.off_part = off;
   off += align256(part_res > part_str ? part_res : part_str);
   p.off_cfin = off;
@@ -127,7 +127,7 @@ static bool device_fits_resident() {
   if (cached[dev] == 0) {
     int cus = 0;
     const hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    cached[dev] = (e == hipSuccess && cus >= kResidentGrid) ? 1 : 2;
+    cached[dev] = (e == hipSuccess && cus >= kResidentCUs) ? 1 : 2;
   }
   return cached[dev] == 1;
 }
@@ -169,6 +169,7 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       ra.part = reinterpret_cast<float2*>(ws + plan.off_part);
       ra.cnt = reinterpret_cast<int32_t*>(ws + plan.off_cnt);
       ra.err = ra.cnt + ra.U;
+      ra.go = ra.cnt + ra.U + 1;
       ra.dbg = reinterpret_cast<long long*>(ws + plan.off_dbg);
       ra.L = nl; ra.B = d.B; ra.Hq = d.Hq; ra.Hkv = d.Hkv; ra.G = plan.G; ra.alpha = d.alpha; ra.N = d.N;
       ra.R = plan.R; ra.Rpad = plan.res_Rpad; ra.nrb = plan.res_nrb; ra.TPU = plan.TPU; ra.UPR = plan.UPR;
@@ -177,6 +178,7 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       ra.q_sb = d.q_sb; ra.q_sh = d.q_sh; ra.q_st = d.q_st;
       ra.kv_sb = d.kv_sb; ra.kv_sh = d.kv_sh; ra.kv_st = d.kv_st;
       ra.kappa = kappa;
+      ra.inv_kappa = 1.0f / kappa;
       ra.inv_G = 1.0f / (float)plan.G;
       if (launch_score_resident(ra, stream) != hipSuccess) return PKV_ERR_HIP;
       if (rec) rec->after(PKV_KERNEL_SCORE_RESIDENT, stream);

@@ -57,8 +57,9 @@ struct ScoreArgs {
 
 
 // ---- register-resident scoring over many layers (pkv_resident.hip) ----
-constexpr int kResidentGrid = 256;      // persistent workgroups, one per compute unit
-constexpr int kResidentKeys = 1024;     // keys held in registers by one workgroup
+constexpr int kResidentCUs = 256;       // compute units the persistent grid is sized for
+constexpr int kResidentGrid = 512;      // persistent workgroups: two per compute unit, one wave per SIMD each
+constexpr int kResidentKeys = 512;      // keys held in registers by one workgroup (4 waves x 4 tiles x 32)
 constexpr int kResidentMaxRows = 1024;  // G * alpha (padded to 128) the LDS normaliser table can hold
 constexpr int kResidentMaxLayers = 96;  // per launch (kernel-argument table)
 
@@ -76,10 +77,11 @@ struct ResidentArgs {
   float2* part;   // [U][TPU][Rpad] per-part softmax statistics (log2 domain)
   int32_t* cnt;   // [U] arrivals per unit; zeroed by the launcher
   int32_t* err;   // == cnt + U: set to 1 if a bounded wait gave up
+  int32_t* go;    // == cnt + U + 1: start signal for the second set of workgroups
   long long* dbg; // per-workgroup phase timers (development builds only), may be null
   int32_t L, B, Hq, Hkv, G, alpha, N, R, Rpad, nrb, TPU, UPR, U, nrounds, d;
   int64_t q_sb, q_sh, q_st, kv_sb, kv_sh, kv_st;
-  float kappa, inv_G;
+  float kappa, inv_kappa, inv_G;
 };
 
 // ---- pooling + selection and gather over many layers ----

@@ -40,6 +40,18 @@ def kernel_bytes(name, w, ks, sum_n):
     return 0
 
 
+def measured_traffic(kernel, workload, avg):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (profiles/traffic_bytes.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic_bytes.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 4 and not line.startswith("#") and f[0] == kernel and f[1] == workload and int(f[2]) == avg:
+            return int(f[3])
+    return None
+
+
 def cpu_baseline(w, ks, layers_host, lens, budget_s=12.0):
     """The oracle, as it stands, on the host cores, on a bounded sample of layers of the same workload."""
     from oracle import pkv_oracle
@@ -145,7 +157,8 @@ def main():
         "whole_path": {"achieved_GBps": total_bytes / (ms_per_step * 1e-3) / 1e9,
                        "frac_of_hbm_peak": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "roofline": {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": measured_traffic(dominant, w.name, avg),
                      "algorithmic_bytes_per_launch": sweep_bytes, "avg_launch_ms": avg_ms[dominant]},
         "kernel_ms_per_step": sum_ms,
     }

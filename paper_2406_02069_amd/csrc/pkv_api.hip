@@ -23,8 +23,14 @@ Plan make_plan(const pkv_layer_desc& d, int L) {
   p.res_Rpad = (p.R + 127) / 128 * 128;
   p.res_nrb = p.res_Rpad / 128;
   p.TPU = (d.N + kResidentKeys - 1) / kResidentKeys;
-  p.resident_ok = p.res_Rpad <= kResidentMaxRows && p.TPU <= kResidentGrid;
-  p.UPR = p.resident_ok ? kResidentGrid / p.TPU : 1;
+  // the kernel addresses keys and query rows with 32-bit byte offsets from the head's first element
+  const bool offsets_fit = (int64_t)d.N * d.kv_st * 2 < ((int64_t)1 << 31) &&
+                           ((int64_t)p.G * d.q_sh + (int64_t)d.alpha * d.q_st) * 2 < ((int64_t)1 << 31);
+  p.resident_ok = p.res_Rpad <= kResidentMaxRows && p.TPU <= kResidentGrid && offsets_fit;
+  int gs = 64;  // group size: the smallest power of two >= 64 that holds all parts of a unit
+  while (gs < p.TPU && gs < kResidentGrid) gs *= 2;
+  p.ngroups = kResidentGrid / gs;
+  p.UPG = p.resident_ok ? gs / p.TPU : 1;
   // --- per-layer streaming path ---
   p.RT = p.R <= 32 ? 1 : (p.R <= 64 ? 2 : 4);
   p.RB = 32 * p.RT;
@@ -38,13 +44,16 @@ Plan make_plan(const pkv_layer_desc& d, int L) {
   p.nchunk = (d.N + p.KC - 1) / p.KC;
   // --- workspace: large enough for either path ---
   const size_t U = (size_t)L * p.BH;
-  const size_t part_res = p.resident_ok ? U * p.TPU * p.res_Rpad * sizeof(float2) : 0;
+  const size_t nslots = (size_t)p.ngroups * p.UPG;
+  const size_t part_res = p.resident_ok ? nslots * p.TPU * p.res_Rpad * sizeof(float2) : 0;
   const size_t part_str = (size_t)p.BH * p.Rpad * p.nchunk * sizeof(float2);
   const size_t raw_res = U * d.N * sizeof(float);
   const size_t raw_str = U * p.nrb * d.N * sizeof(float);
   size_t off = 0;
   p.off_cnt = off;
-  off += align256((U + 2) * sizeof(int32_t));
+  // [U counters][error word][pad to 8 bytes][nslots * Rpad tagged normaliser words]
+  p.sync_bytes = ((U + 1) * sizeof(int32_t) + 7) / 8 * 8 + nslots * p.res_Rpad * sizeof(uint64_t);
+  off += align256(p.sync_bytes);
   p.off_part = off;
   off += align256(part_res > part_str ? part_res : part_str);
   p.off_cfin = off;
@@ -54,7 +63,7 @@ Plan make_plan(const pkv_layer_desc& d, int L) {
   p.off_pooled = off;
   off += align256(U * d.N * sizeof(float));
   p.off_dbg = off;
-  off += align256((size_t)kResidentGrid * 8 * sizeof(long long));
+  off += align256(((size_t)kResidentGrid * 8 + 1024) * sizeof(long long));
   p.total = off;
   return p;
 }
@@ -132,6 +141,12 @@ static bool device_fits_resident() {
   return cached[dev] == 1;
 }
 
+// Late start of the second workgroup of each compute unit, in 10 ns ticks (tuning hook: PKV_STAGGER).
+static int resident_stagger() {
+  if (const char* e = getenv("PKV_STAGGER")) return atoi(e);
+  return 500;
+}
+
 static bool use_resident(const Plan& plan) {
   if (const char* e = getenv("PKV_SCORE_PATH")) {  // test hook: "stream" forces the per-layer kernels
     if (!strcmp(e, "stream")) return false;
@@ -169,11 +184,14 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       ra.part = reinterpret_cast<float2*>(ws + plan.off_part);
       ra.cnt = reinterpret_cast<int32_t*>(ws + plan.off_cnt);
       ra.err = ra.cnt + ra.U;
-      ra.go = ra.cnt + ra.U + 1;
+      const size_t cbuf_off = ((size_t)(ra.U + 1) * sizeof(int32_t) + 7) / 8 * 8;
+      ra.cbuf = reinterpret_cast<unsigned long long*>(ws + plan.off_cnt + cbuf_off);
+      ra.sync_words = (int32_t)((cbuf_off + (size_t)plan.ngroups * plan.UPG * plan.res_Rpad * sizeof(uint64_t)) / 4);
       ra.dbg = reinterpret_cast<long long*>(ws + plan.off_dbg);
       ra.L = nl; ra.B = d.B; ra.Hq = d.Hq; ra.Hkv = d.Hkv; ra.G = plan.G; ra.alpha = d.alpha; ra.N = d.N;
-      ra.R = plan.R; ra.Rpad = plan.res_Rpad; ra.nrb = plan.res_nrb; ra.TPU = plan.TPU; ra.UPR = plan.UPR;
-      ra.nrounds = (ra.U + plan.UPR - 1) / plan.UPR;
+      ra.R = plan.R; ra.Rpad = plan.res_Rpad; ra.nrb = plan.res_nrb; ra.TPU = plan.TPU;
+      ra.ngroups = plan.ngroups; ra.UPG = plan.UPG;
+      ra.stagger = resident_stagger();
       ra.d = d.d;
       ra.q_sb = d.q_sb; ra.q_sh = d.q_sh; ra.q_st = d.q_st;
       ra.kv_sb = d.kv_sb; ra.kv_sh = d.kv_sh; ra.kv_st = d.kv_st;

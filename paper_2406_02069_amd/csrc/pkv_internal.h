@@ -28,8 +28,9 @@ struct Plan {
   // register-resident scoring
   bool resident_ok;
   int res_Rpad, res_nrb;  // rows padded to 128-row blocks
-  int TPU;       // 1024-key parts per unit
-  int UPR;       // units per round of 256 workgroups
+  int TPU;       // 512-key parts per unit
+  int ngroups;   // independent workgroup groups (512 / group size)
+  int UPG;       // units in flight per group
   // per-layer streaming scoring
   int RT;        // 32-row MFMA tiles per row block (1, 2 or 4)
   int RB;        // rows per row block: 32 * RT
@@ -39,6 +40,7 @@ struct Plan {
   int nchunk;    // ceil(N / KC)
   // workspace carve-up (byte offsets, each 256-aligned)
   size_t off_cnt, off_part, off_cfin, off_raw, off_pooled, off_dbg, total;
+  size_t sync_bytes;  // counters + error word + tagged normalisers (zeroed before each resident launch)
 };
 
 Plan make_plan(const pkv_layer_desc& d, int L);
@@ -73,13 +75,17 @@ struct ResidentLayer {
 struct ResidentArgs {
   ResidentLayer layer[kResidentMaxLayers];
   const int32_t* seq_lens;
-  float* raw;     // [L][BH][N] un-pooled scores
-  float2* part;   // [U][TPU][Rpad] per-part softmax statistics (log2 domain)
-  int32_t* cnt;   // [U] arrivals per unit; zeroed by the launcher
+  float* raw;     // [U][N] un-pooled scores
+  float2* part;   // [nslots][TPU][Rpad] per-part softmax statistics (log2 domain), reused from unit to unit
+  int32_t* cnt;   // [U] arrivals per unit; start of the zeroed synchronisation words
   int32_t* err;   // == cnt + U: set to 1 if a bounded wait gave up
-  int32_t* go;    // == cnt + U + 1: start signal for the second set of workgroups
+  unsigned long long* cbuf;  // [nslots][Rpad] (unit tag << 32 | normaliser bits), behind err, 8-byte aligned
   long long* dbg; // per-workgroup phase timers (development builds only), may be null
-  int32_t L, B, Hq, Hkv, G, alpha, N, R, Rpad, nrb, TPU, UPR, U, nrounds, d;
+  int32_t sync_words;  // 32-bit words to zero before the launch: counters, error word, cbuf
+  int32_t L, B, Hq, Hkv, G, alpha, N, R, Rpad, nrb, TPU, U, d;
+  int32_t ngroups;  // independent groups of workgroups: 512 / group size
+  int32_t UPG;      // units a group works on at the same time: group size / TPU
+  int32_t stagger;  // late start of the second workgroup of each compute unit, in 10 ns ticks
   int64_t q_sb, q_sh, q_st, kv_sb, kv_sh, kv_st;
   float kappa, inv_kappa, inv_G;
 };

@@ -4,26 +4,37 @@
 // The score of a key needs the softmax normaliser of every window query, which is known only after
 // all keys of the head have been seen; so the product Q K^T has to be formed twice (statistics, then
 // normalised scores).  Re-reading K for the second sweep costs as much as the first (the 4 MB L2 per
-// XCD cannot hold a head, and the memory-side cache is no faster than HBM), so K stays on chip
-// between the sweeps instead: persistent 256-thread workgroups, two per compute unit, each hold 512
-// keys as MFMA operand fragments in their vector registers (4 waves x 4 tiles x 32 keys; 512
-// workgroups x 512 keys = 8 KV heads x 32768 keys, a whole Llama-3-8B layer at 32k context).
+// XCD cannot hold a head, and the memory-side cache streams no faster than HBM), so K stays on chip
+// between the sweeps: 512 persistent 256-thread workgroups, two per compute unit, each hold 512 keys
+// as MFMA operand fragments in their vector registers (4 waves x 4 tiles x 32 keys).
 //
-// A "task" is (unit = layer x sequence x KV head, 512-key part).  Tasks are handed out in rounds of
-// up to 512 (one per workgroup); a unit never straddles a round.  Per round a workgroup
-//   1. loads its keys: coalesced 16-byte global loads -> wave-private swizzled LDS tile -> fragments;
-//   2. sweep 1: for every 32-row tile of Q (staged in LDS, used as the second MFMA operand) and every
-//      resident key tile, logits -> running (max, sum exp2) per query row; the 4 waves are merged in
-//      LDS and the per-part statistics written to global memory;
-//   3. unit barrier: an agent-scope counter per unit; when all parts of the unit have arrived every
-//      workgroup of the unit folds the parts into the per-row normaliser c_r = max + log2(sum);
+// Work split.  A "unit" is (layer, sequence, KV head); it is cut into parts of 512 keys, one part per
+// workgroup.  The grid is divided into groups of 64..512 workgroups (the smallest power of two that
+// holds a unit); a group works through its own list of units at its own pace, so groups drift apart
+// and while one streams keys from HBM others compute.  The two workgroups of a compute unit belong to
+// different groups, and the second set of groups starts late, so that a compute unit rarely has both
+// of its workgroups waiting at the same time.
+//
+// Per unit a workgroup
+//   1. loads its keys straight into MFMA operand layout (each lane: 16 bytes of one key row per
+//      load; 32 loads in flight per lane) and stages the 128-row block of Q in LDS;
+//   2. sweep 1: for every 32-row tile of Q and every resident 32-key tile, logits -> per-row
+//      (reference, sum exp2) per lane; merged over the wave halves, the 4 waves (LDS) and written as the
+//      part's statistics;
+//   3. arrives at the unit's counter.  The last part to arrive folds all parts into the per-row
+//      normaliser c_r = max + log2(sum) and publishes it, tagged with the unit number; the others poll
+//      the tagged words.  (Agent-scope relaxed atomics: written through, never served from a stale line.)
 //   4. sweep 2: same products from the same registers, s_i = sum_r exp2(kappa q_r.k_i - c_r), written
 //      once per key (already divided by the group size).
-// Products are 16x16x32 MFMAs (4 accumulator registers each): the matrix work of the next 16x16
-// product is issued in between the exponentials of the current one, so the MFMA and the vector pipes
-// run side by side inside a wave, and the register budget (128 for K, 32 for Q) leaves room for it.
-// With blockIdx -> XCD round-robin placement the parts of a unit sit on one XCD whenever 64 is a
-// multiple of the parts per unit, so the barrier traffic stays in that XCD's L2.
+//
+// Inner loops.  Products are v_mfma_f32_32x32x16_bf16 (the 16x16x32 shape does not overlap with vector
+// work on this chip and runs at two thirds of the rate).  A sweep is bound by the vector pipe: per
+// logit one multiply-add, one v_exp_f32 and one add.  The 8 MFMAs of the next 32x32 product are issued
+// one by one between the exponentials of the current product (explicit scheduling groups), so the
+// matrix pipe runs in the shadow of the vector pipe.  Sweep 1 uses a provisional per-lane reference
+// exponent taken from the first tile instead of a running maximum (no branch, no second exponential);
+// a row tile whose sums leave a safe range is recomputed with the exact running-maximum update, and so
+// are tiles that touch the causal window or the end of the sequence (they need masks).
 //
 // Every wait is bounded: a workgroup that spins too long raises the error word and carries on, so the
 // grid always drains.  The launch uses exactly 512 workgroups, two per compute unit (register- and
@@ -35,32 +46,32 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 // 16 bytes as a native vector (HIP's uint4 class keeps such values out of registers when staged in arrays)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
 
 constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
-constexpr int kTilesPerWave = 4;
-constexpr int kRowBlock = 128;
-constexpr long long kSpinLimit = 1ll << 22;
-constexpr long long kGoSpinLimit = 1ll << 16;  // start-up stagger only: giving up early is harmless
+constexpr int kTiles = 4;          // 32-key tiles held by one wave
+constexpr int kRowBlock = 128;     // rows of Q staged in LDS at a time
+constexpr int kSpinLimit = 1 << 20;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-#define PKV_MFMA16(A, B, C) __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, C, 0, 0, 0)
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 __device__ __forceinline__ bf16x8 as_frag(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
+#define PKV_MFMA32(A, B, C) __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, C, 0, 0, 0)
+// scheduling groups: the next N instructions of a class, in this order
+#define PKV_SG_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
+#define PKV_SG_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
+#define PKV_SG_TRANS(n) __builtin_amdgcn_sched_group_barrier(0x400, n, 0)
+#define PKV_SG_DSR(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
 
+// The Q block is kept in LDS with a row pitch of SEG + 1 sixteen-byte segments: consecutive rows then
+// start 4 banks apart (mod 64), so the 16 rows that one ds_read_b128 phase touches hit all banks once,
+// and the segment index stays a compile-time address offset.
 template <int SEG>
-__device__ __forceinline__ int lds_slot(int row, int seg) {
-  const int swz = (SEG == 16) ? (row & 15) : ((row >> 1) & 7);
-  return row * SEG + (seg ^ swz);
-}
-
-__device__ __forceinline__ void wave_lds_fence() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
+__device__ __forceinline__ constexpr int lds_pitch() { return SEG + 1; }
 
 __device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float z2) {
   const float M = fmaxf(m, m2);
@@ -69,104 +80,80 @@ __device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float 
   m = M;
 }
 
-// One 32-key tile as loaded from global memory: NLD wave-wide 16-byte loads (row-major, coalesced).
-template <int NLD>
-struct RawTile {
-  u32x4 v[NLD];
-};
+__device__ __forceinline__ void st64(u64* p, u64 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ u64 ld64(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-template <int SEG>
-__device__ __forceinline__ RawTile<SEG / 2> load_raw_tile(const uint16_t* Kbase, int64_t kv_st, int row0, int n,
-                                                           bool whole, int lane) {
-  constexpr int NLD = SEG / 2, RPL = 64 / SEG;  // RPL rows per wave-wide load
-  const int lrow = lane / SEG, lseg = lane - lrow * SEG;
-  RawTile<NLD> r;
-  if (whole) {  // wave-uniform row pointer + one per-lane offset
-    const uint32_t loff = (uint32_t)lrow * (uint32_t)kv_st + (uint32_t)lseg * 8u;
-#pragma unroll
-    for (int i = 0; i < NLD; ++i)
-      r.v[i] = *reinterpret_cast<const u32x4*>(Kbase + (size_t)(row0 + RPL * i) * kv_st + loff);
-  } else {  // clamp: rows at or beyond n are never read
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int key = min(row0 + RPL * i + lrow, n - 1);
-      r.v[i] = *reinterpret_cast<const u32x4*>(Kbase + (size_t)key * kv_st + lseg * 8);
-    }
-  }
-  return r;
-}
-
-// Row-major tile -> wave-private swizzled LDS tile -> 16x16x32 MFMA operand fragments of this lane:
-// fragment [ns * KS + ks] holds, for key 16*ns + (lane & 15), the 8 elements at 32*ks + 8*(lane >> 4).
-template <int SEG>
-__device__ __forceinline__ void raw_to_frags(const RawTile<SEG / 2>& r, u32x4* tile, int lane, bf16x8 (&kf)[SEG / 2]) {
-  constexpr int NLD = SEG / 2, KS = SEG / 4;
-  const int l16 = lane & 15, kq = lane >> 4;
-#pragma unroll
-  for (int i = 0; i < NLD; ++i) {
-    const int e = i * 64 + lane;
-    const int row = e / SEG, seg = e - row * SEG;
-    tile[lds_slot<SEG>(row, seg)] = r.v[i];
-  }
-  wave_lds_fence();
-#pragma unroll
-  for (int ns = 0; ns < 2; ++ns)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) kf[ns * KS + ks] = as_frag(tile[lds_slot<SEG>(16 * ns + l16, 4 * ks + kq)]);
-  wave_lds_fence();
-}
+// Accumulator element v of a lane (half h) belongs to tile row mrow(v, h) (32x32 MFMA output layout).
+__device__ __forceinline__ constexpr int mrow0(int v) { return 8 * (v >> 2) + (v & 3); }
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const ResidentArgs a) {
-  constexpr int KS = D / 32;   // 16x16x32 MFMA k-steps per dot product
+  constexpr int KS = D / 16;   // 32x32x16 MFMA k-steps per dot product
   constexpr int SEG = D / 8;   // 16-byte segments per row
-  constexpr int NLD = SEG / 2; // wave-wide global loads per 32-key tile
-  constexpr int NF = 2 * KS;   // fragments per 32-row / 32-key tile
-  constexpr int TILE_U4 = 32 * SEG;
-  constexpr int NSUB = kTilesPerWave * 4;  // 16x16 products per 32-row tile of Q
-  __shared__ u32x4 kstage[kWaves * TILE_U4];     // one landing tile per wave
-  __shared__ u32x4 qs[kRowBlock * SEG];          // current 128-row block of Q
+  constexpr int TPM = 16 / KS; // logits per lane handled between two MFMAs
+  constexpr int PITCH = lds_pitch<SEG>();
+  constexpr int QLD = kRowBlock * SEG / kThreads;  // 16-byte loads per thread for one block of Q
+  constexpr int RPP = kThreads / SEG;              // rows covered by one pass of the workgroup
+  __shared__ u32x4 qs[kRowBlock * PITCH];        // current 128-row block of Q
   __shared__ float2 red[kWaves][kRowBlock];
-  __shared__ float cst[kResidentMaxRows];
+  __shared__ __attribute__((aligned(16))) float cst[kResidentMaxRows];
   __shared__ int qoff[kRowBlock];
+  __shared__ int s_last;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps addressing in scalar registers
-  const int l16 = lane & 15;
-  const int kq = lane >> 4;
-  const f32x4 kZero4 = {0.f, 0.f, 0.f, 0.f};
-
-  // Two sets of 256 workgroups.  With round-robin placement (block -> XCD blockIdx % 8, then one block
-  // per CU before a CU gets its second) the two workgroups of a CU belong to different sets.  Inside a
-  // set the workgroups of one XCD take consecutive tasks.  Set 1 starts half a round late (below), so
-  // that on every CU one workgroup streams keys or waits at a unit barrier while the other computes.
-  const int kk_ = blockIdx.x >> 3;
-  const int set = kk_ / (kResidentGrid / 16);
-  const int pos = set * (kResidentGrid / 2) + (blockIdx.x & 7) * (kResidentGrid / 16) + kk_ % (kResidentGrid / 16);
+  const int l32 = lane & 31;
+  const int hf = lane >> 5;
   const int BH = a.B * a.Hkv;
-  u32x4* tile = kstage + wave * TILE_U4;
+
+  // ---- which group, which slot ----
+  // blockIdx -> XCD is blockIdx % 8, and an XCD fills every compute unit once before any gets a second
+  // workgroup; so set 0 / set 1 are the first / second workgroup of each compute unit.  (Only speed
+  // depends on this placement, never the result.)
+  const int xcd = blockIdx.x & 7, kk = blockIdx.x >> 3;
+  const int set = kk >> 5, cu = kk & 31;
+  int group, slot;
+  if (a.ngroups >= 2) {
+    const int xpc = 16 / a.ngroups;  // XCDs per group cluster
+    group = (xcd / xpc) * 2 + set;
+    slot = (xcd % xpc) * 32 + cu;
+  } else {
+    group = 0;
+    slot = set * 256 + xcd * 32 + cu;
+  }
+  const int sub = slot / a.TPU;
+  const int part_id = slot - sub * a.TPU;
+  if (sub >= a.UPG) return;  // no work for this workgroup at this shape
+  const int slot_id = group * a.UPG + sub;  // one of nslots concurrent units
+  const int nslots = a.ngroups * a.UPG;
+  float2* part_base = a.part + (size_t)slot_id * a.TPU * a.Rpad;
+  u64* cbuf = a.cbuf + (size_t)slot_id * a.Rpad;
 
 #ifdef PKV_RES_TIMING
   long long tstamp[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#define PKV_T(i) tstamp[i] += wall_clock64()
-#define PKV_TN(i) tstamp[i] -= wall_clock64()
+  tstamp[5] = -(long long)clock64();
+  tstamp[6] = -(long long)wall_clock64();
+  // absolute phase-boundary times of a few workgroups (the two of one compute unit, on two XCDs)
+  const int trace_id = (blockIdx.x == 0) ? 0 : (blockIdx.x == 256) ? 1 : (blockIdx.x == 1) ? 2 : (blockIdx.x == 257) ? 3 : -1;
+  int trace_n = 0;
+#define PKV_TRACE() do { if (trace_id >= 0 && trace_n < 240 && tid == 0 && a.dbg) a.dbg[kResidentGrid * 8 + trace_id * 256 + trace_n] = wall_clock64(); ++trace_n; } while (0)
+#define PKV_T(i) do { tstamp[i] += wall_clock64(); PKV_TRACE(); } while (0)
+#define PKV_TN(i) do { tstamp[i] -= wall_clock64(); if (i == 0) PKV_TRACE(); } while (0)
 #else
 #define PKV_T(i)
 #define PKV_TN(i)
 #endif
-  bool first = true;
-  if (set == 1 && tid == 0) {  // bounded wait for the first set-0 workgroup to finish its first sweep
-    long long spins = 0;
-    while (__hip_atomic_load(a.go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0 && ++spins < kGoSpinLimit)
-      __builtin_amdgcn_s_sleep(8);
+
+#ifdef PKV_RES_TIMING
+  if (set == 1 && a.stagger < 0) return;  // measurement: one workgroup per compute unit
+#endif
+  if (set == 1 && a.stagger > 0) {  // late start of the second set: a plain timed wait
+    const long long t0 = wall_clock64();
+    while (wall_clock64() - t0 < a.stagger) __builtin_amdgcn_s_sleep(16);
   }
-  __syncthreads();
-  for (int round = 0; round < a.nrounds; ++round) {
-    if (pos >= a.UPR * a.TPU) break;  // idle in every round
-    const int u = round * a.UPR + pos / a.TPU;
-    const int part_id = pos % a.TPU;
-    if (u >= a.U) break;
+
+  for (int u = slot_id; u < a.U; u += nslots) {
     const int l = u / BH;
     const int bg = u - l * BH;
     const int b = bg / a.Hkv;
@@ -181,129 +168,199 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     if (key0 >= n) continue;            // no keys here; this part is not counted below
     const int nparts = (n + kResidentKeys - 1) / kResidentKeys;
     const int npre = n - a.alpha;
-    const int wkey0 = key0 + wave * (kTilesPerWave * 32);
+    const int wkey0 = key0 + wave * (kTiles * 32);
+    const bool has_keys = wkey0 < n;                      // wave-uniform
+    const bool whole = wkey0 + kTiles * 32 <= n;
+    // tile t needs masks iff it reaches beyond the prefix (causal window, end of the sequence)
+    int dirty_mask = 0;
+#pragma unroll
+    for (int t = 0; t < kTiles; ++t) dirty_mask |= (wkey0 + 32 * t + 32 > npre) ? (1 << t) : 0;
     const uint16_t* Qbase = a.layer[l].Q + (size_t)b * a.q_sb + (size_t)(g * a.G) * a.q_sh;
     const uint16_t* Kbase = a.layer[l].K + (size_t)b * a.kv_sb + (size_t)g * a.kv_sh;
 
-    // Stage a 128-row block of Q in LDS.  qoff[row] = element offset of the row (-1: padding row).
-    auto stage_q = [&](int rb) {
+    // Stage a 128-row block of Q in LDS.  qoff[row] = byte offset of the row (-1: padding row).
+    // Thread -> (row tid / SEG + RPP * i, segment tid % SEG): 16 bytes per load, rows fully coalesced.
+    const int q_row0 = tid / SEG, q_seg = tid - q_row0 * SEG;
+    auto stage_q_issue = [&](int rb, u32x4 (&v)[QLD]) {
       if (tid < kRowBlock) {
         const int r = rb * kRowBlock + tid;
         int off = -1;
         if (r < a.R) {
           const int hh = r / a.alpha, t = r - hh * a.alpha;
-          off = (int)(hh * a.q_sh + t * a.q_st);
+          off = (int)(hh * a.q_sh + t * a.q_st) * 2;
         }
         qoff[tid] = off;
       }
       __syncthreads();
-#pragma unroll 1
-      for (int e = tid; e < kRowBlock * SEG; e += kThreads) {
-        const int row = e / SEG, seg = e - row * SEG;
-        const int off = qoff[row];
-        u32x4 v = u32x4{0u, 0u, 0u, 0u};
-        if (off >= 0) v = *reinterpret_cast<const u32x4*>(Qbase + off + seg * 8);
-        qs[lds_slot<SEG>(row, seg)] = v;
+      const char* qb = reinterpret_cast<const char*>(Qbase) + q_seg * 16;
+#pragma unroll
+      for (int i = 0; i < QLD; ++i) {
+        const int off = qoff[q_row0 + RPP * i];
+        v[i] = u32x4{0u, 0u, 0u, 0u};
+        if (off >= 0) v[i] = *reinterpret_cast<const u32x4*>(qb + (uint32_t)off);
       }
     };
+    auto stage_q_commit = [&](const u32x4 (&v)[QLD]) {
+      u32x4* dst = qs + q_row0 * PITCH + q_seg;
+#pragma unroll
+      for (int i = 0; i < QLD; ++i) dst[RPP * i * PITCH] = v[i];
+    };
 
-    // ---- 1. keys -> registers ----
+    // ---- 1. Q block 0 -> LDS, keys -> registers (fragment layout, no staging) ----
     PKV_TN(0);
-    bf16x8 kf[kTilesPerWave][NF];
+    bf16x8 kf[kTiles][KS];
     {
-      // Two tiles of global loads (and the Q block) are in flight while an earlier tile goes through LDS.
-      const bool whole = wkey0 + kTilesPerWave * 32 <= n;
-      RawTile<NLD> ra = load_raw_tile<SEG>(Kbase, a.kv_st, wkey0, n, whole, lane);
-      RawTile<NLD> rb = load_raw_tile<SEG>(Kbase, a.kv_st, wkey0 + 32, n, whole, lane);
-      stage_q(0);
-      raw_to_frags<SEG>(ra, tile, lane, kf[0]);
-      ra = load_raw_tile<SEG>(Kbase, a.kv_st, wkey0 + 64, n, whole, lane);
-      raw_to_frags<SEG>(rb, tile, lane, kf[1]);
-      rb = load_raw_tile<SEG>(Kbase, a.kv_st, wkey0 + 96, n, whole, lane);
-      raw_to_frags<SEG>(ra, tile, lane, kf[2]);
-      raw_to_frags<SEG>(rb, tile, lane, kf[3]);
+      u32x4 qv[QLD];
+      stage_q_issue(0, qv);  // issued first: loads return in order, and the Q block is needed first
+      if (has_keys) {
+        // 32-bit byte offsets from the head's first key (the host admits only shapes where they fit)
+        const char* kb = reinterpret_cast<const char*>(Kbase) + 16 * hf;
+        const uint32_t row_bytes = (uint32_t)a.kv_st * 2u;
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t) {
+          int key = wkey0 + 32 * t + l32;
+          if (!whole) key = min(key, n - 1);  // rows at or beyond n are never read
+          const char* rowp = kb + (uint32_t)key * row_bytes;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) kf[t][ks] = as_frag(*reinterpret_cast<const u32x4*>(rowp + 32 * ks));
+        }
+      }
+      stage_q_commit(qv);
     }
+    __syncthreads();
     PKV_T(0);
     PKV_TN(1);
 
+    // LDS reads of one 32-row tile of Q as MFMA operand fragments
+    const u32x4* q_lane = qs + l32 * PITCH + hf;
+    auto q_frag = [&](int rt, int ks) { return as_frag(q_lane[32 * rt * PITCH + 2 * ks]); };
+
     // ---- 2. sweep 1: per-row statistics over this workgroup's keys ----
-    // Sub-product i = (t, ns, ms) of a 32-row tile: keys 32t+16ns.., query rows 16ms..; the product's
-    // rows are keys (lane holds keys 4*kq..+3 of the sub-tile), its columns query rows (lane & 15).
-    float2* part = a.part + ((size_t)u * a.TPU + part_id) * a.Rpad;
+    // Products: rows = keys (element v of a lane: key mrow0(v) + 4*hf of the tile), columns = query rows
+    // (lane & 31).  Per lane and row tile: reference exponent m (log2 domain) and z = sum exp2(x - m).
+    float2* part = part_base + (size_t)part_id * a.Rpad;
     for (int rb = 0; rb < a.nrb; ++rb) {
-      if (rb > 0) stage_q(rb);
-      __syncthreads();
+      if (rb > 0) {
+        u32x4 qv[QLD];
+        __syncthreads();  // everyone is done with the previous block
+        stage_q_issue(rb, qv);
+        stage_q_commit(qv);
+        __syncthreads();
+      }
       const int rows_here = min(kRowBlock, a.R - rb * kRowBlock);
       const int nrt = (rows_here + 31) / 32;
-      bf16x8 qf[NF];
+      if (has_keys) {
+        // exact update of (m, z) with the 16 logits of one product; masked elements excluded
+        auto exact_update = [&](const f32x16& acc, int t, bool masked, int lim_rel, float& m, float& z) {
+          float x[16];
+          float tm = -INFINITY;
 #pragma unroll
-      for (int ms = 0; ms < 2; ++ms)
+          for (int v = 0; v < 16; ++v) {
+            x[v] = acc[v] * a.kappa;
+            if (masked && 32 * t + mrow0(v) > lim_rel) x[v] = -INFINITY;
+            tm = fmaxf(tm, x[v]);
+          }
+          const float mn = fmaxf(m, tm);
+          const float ms = (mn == -INFINITY) ? 0.f : mn;
+          float s = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ms * KS + ks] = as_frag(qs[lds_slot<SEG>(16 * ms + l16, 4 * ks + kq)]);
-      f32x4 acc_cur = kZero4, acc_nxt;
+          for (int v = 0; v < 16; ++v) s += fast_exp2(x[v] - ms);
+          z = z * fast_exp2(m - ms) + s;
+          m = mn;
+        };
+        auto finish_rt = [&](int rt, float m, float z) {
+          const float m2 = __shfl_xor(m, 32), z2 = __shfl_xor(z, 32);
+          merge_stats(m, z, m2, z2);
+          if (hf == 0) red[wave][32 * rt + l32] = make_float2(m, z);
+        };
+        // last key (relative to this wave's first key and half) that the lane's query of row tile rt sees
+        auto lim_rel_of = [&](int rt) {
+          const int r = rb * kRowBlock + 32 * rt + l32;
+          const int lim = (r < a.R) ? npre + (r % a.alpha) : npre + a.alpha - 1;  // padding rows: statistics unused
+          return lim - wkey0 - 4 * hf;
+        };
+
+        bf16x8 qf[KS];
+        f32x16 cur, nxt;
+        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) acc_cur = PKV_MFMA16(kf[0][ks], qf[ks], acc_cur);
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = q_frag(0, ks);
+        cur = zero16;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) cur = PKV_MFMA32(kf[0][ks], qf[ks], cur);
+        int redo = 0;  // row tiles whose provisional reference failed (wave-uniform bit mask)
 #pragma unroll 1
-      for (int rt = 0; rt < nrt; ++rt) {
-        const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;  // after the last tile one unused product is issued
-        // Running statistics of this lane's two query rows over this lane's keys, relative to a reference
-        // exponent sm that is only raised when a product would overflow it (the common case costs one
-        // fma, one exp2 and one add per logit).
-        float sm[2] = {-INFINITY, -INFINITY}, sz[2] = {0.f, 0.f};
-        int limit[2];
+        for (int rt = 0; rt < nrt; ++rt) {
+          const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;  // after the last tile one unused product is issued
+          float m = -INFINITY, z = 0.f;  // m: reference exponent of this lane (not necessarily the maximum)
+          const int lim_rel = lim_rel_of(rt);
 #pragma unroll
-        for (int ms = 0; ms < 2; ++ms) {
-          const int r = rb * kRowBlock + 32 * rt + 16 * ms + l16;
-          limit[ms] = (r < a.R) ? npre + (r % a.alpha) : -1;  // last key this query sees (causal)
-        }
+          for (int t = 0; t < kTiles; ++t) {
+            const int tn = (t + 1) % kTiles;
+            if (dirty_mask & (1 << t)) {
+              // slow variant of the step (masks, exact update); the next product is still issued first
+              nxt = zero16;
 #pragma unroll
-        for (int i = 0; i < NSUB; ++i) {
-          const int t = i >> 2, ns = (i >> 1) & 1, ms = i & 1;
-          const int j = (i + 1) % NSUB, tj = j >> 2, nsj = (j >> 1) & 1, msj = j & 1;
-          const int sub_base = wkey0 + 32 * t + 16 * ns;
-          if (sub_base + 16 > npre) {  // touches the window or the end of the sequence
+              for (int ks = 0; ks < KS; ++ks) {
+                nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
+                if (t == kTiles - 2) qf[ks] = q_frag(rt_next, ks);
+              }
+              exact_update(cur, t, true, lim_rel, m, z);
+            } else {
+              float nref;
+              if (t == 0) {  // provisional reference: the largest of three of the lane's logits
+                m = a.kappa * fmaxf(fmaxf(cur[0], cur[5]), cur[10]);
+                z = 0.f;
+              }
+              nref = -m;
+              float s0 = 0.f, s1 = 0.f;
+              nxt = zero16;
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-              if (sub_base + 4 * kq + v > limit[ms]) acc_cur[v] = -INFINITY;
+              for (int ks = 0; ks < KS; ++ks) {
+                nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
+                if (t == kTiles - 2) qf[ks] = q_frag(rt_next, ks);  // last use of this fragment was the MFMA above
+                float x[TPM], e[TPM];
+#pragma unroll
+                for (int j = 0; j < TPM; ++j) x[j] = __builtin_fmaf(cur[TPM * ks + j], a.kappa, nref);
+#pragma unroll
+                for (int j = 0; j < TPM; ++j) e[j] = fast_exp2(x[j]);
+#pragma unroll
+                for (int j = 0; j < TPM; ++j) {
+                  if (j & 1) s1 += e[j]; else s0 += e[j];
+                }
+                PKV_SG_MFMA(1);
+                if (t == kTiles - 2) PKV_SG_DSR(1);
+                PKV_SG_VALU(TPM);
+                PKV_SG_TRANS(TPM);
+                PKV_SG_VALU(TPM);
+              }
+              z += s0 + s1;
+            }
+            cur = nxt;
           }
-          if (i >= NSUB - 2) {  // the Q fragments of this half tile are free: fetch the next row tile's
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-              qf[(i & 1) * KS + ks] = as_frag(qs[lds_slot<SEG>(32 * rt_next + 16 * (i & 1) + l16, 4 * ks + kq)]);
-          }
-          acc_nxt = kZero4;
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) acc_nxt = PKV_MFMA16(kf[tj][nsj * KS + ks], qf[msj * KS + ks], acc_nxt);
-          const float nref = -sm[ms];
-          float e0 = fast_exp2(__builtin_fmaf(acc_cur[0], a.kappa, nref));
-          float e1 = fast_exp2(__builtin_fmaf(acc_cur[1], a.kappa, nref));
-          float e2 = fast_exp2(__builtin_fmaf(acc_cur[2], a.kappa, nref));
-          float e3 = fast_exp2(__builtin_fmaf(acc_cur[3], a.kappa, nref));
-          float sum = (e0 + e1) + (e2 + e3);
-          if (__any(!(sum <= 0x1p60f))) {
-            // first product, masked product, or a logit far above the reference: exact update
-            const float tm = fmaxf(fmaxf(acc_cur[0], acc_cur[1]), fmaxf(acc_cur[2], acc_cur[3]));
-            const float mn = fmaxf(sm[ms], tm * a.kappa);
-            const float mz = (mn == -INFINITY) ? 0.f : mn;
-            sum = 0.f;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) sum += fast_exp2(__builtin_fmaf(acc_cur[v], a.kappa, -mz));
-            sz[ms] = sz[ms] * fast_exp2(sm[ms] - mz) + sum;
-            sm[ms] = mn;
-          } else {
-            sz[ms] += sum;
-          }
-          acc_cur = acc_nxt;
+          // a sum outside the safe range (or NaN) means the provisional reference was too far off
+          if (__any(!(z <= 0x1p100f))) redo |= 1 << rt;
+          finish_rt(rt, m, z);
         }
+        // rare: recompute flagged row tiles with the exact running-maximum update (pipeline is drained here)
+        for (int rt = 0; redo != 0 && rt < nrt; ++rt) {
+          if (!(redo & (1 << rt))) continue;
+          bf16x8 q2[KS];
 #pragma unroll
-        for (int ms = 0; ms < 2; ++ms) {
-          // the 4 lanes with equal (lane & 15) hold the same query row over different keys
-          float m2 = __shfl_xor(sm[ms], 16), z2 = __shfl_xor(sz[ms], 16);
-          merge_stats(sm[ms], sz[ms], m2, z2);
-          m2 = __shfl_xor(sm[ms], 32), z2 = __shfl_xor(sz[ms], 32);
-          merge_stats(sm[ms], sz[ms], m2, z2);
-          if (kq == 0) red[wave][32 * rt + 16 * ms + l16] = make_float2(sm[ms], sz[ms]);
+          for (int ks = 0; ks < KS; ++ks) q2[ks] = q_frag(rt, ks);
+          float m = -INFINITY, z = 0.f;
+          const int lim_rel = lim_rel_of(rt);
+#pragma unroll
+          for (int t = 0; t < kTiles; ++t) {
+            f32x16 acc = zero16;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc = PKV_MFMA32(kf[t][ks], q2[ks], acc);
+            exact_update(acc, t, (dirty_mask >> t) & 1, lim_rel, m, z);
+          }
+          finish_rt(rt, m, z);
         }
+      } else {
+        for (int r = lane; r < kRowBlock; r += 64) red[wave][r] = make_float2(-INFINITY, 0.f);
       }
       __syncthreads();
       if (tid < rows_here) {
@@ -311,36 +368,21 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) merge_stats(m, z, red[w][tid].x, red[w][tid].y);
         // device-scope store: written through, so that other XCDs see it without an L2 write-back
-        const unsigned long long bits = ((unsigned long long)__float_as_uint(z) << 32) | __float_as_uint(m);
-        __hip_atomic_store(reinterpret_cast<unsigned long long*>(part + rb * kRowBlock + tid), bits, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+        st64(reinterpret_cast<u64*>(part + rb * kRowBlock + tid), ((u64)__float_as_uint(z) << 32) | __float_as_uint(m));
       }
-      __syncthreads();  // also waits for the stores above to be acknowledged
     }
-
+    __syncthreads();  // also waits for the stores above to be acknowledged
     PKV_T(1);
     PKV_TN(2);
-    // ---- 3. unit barrier, then fold the parts into the per-row normaliser ----
-    // (the statistics were written through and acknowledged before the workgroup barrier that ends
-    // sweep 1, so the arrival counter needs no cache write-back of its own)
+
+    // ---- 3. arrive; the last part folds all parts into the per-row normaliser and publishes it ----
+    const unsigned tag = (unsigned)u + 1u;
     if (tid == 0) {
-      if (first && set == 0) __hip_atomic_store(a.go, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_fetch_add(&a.cnt[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      long long spins = 0;
-      while (__hip_atomic_load(&a.cnt[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nparts) {
-        __builtin_amdgcn_s_sleep(2);
-        if (++spins > kSpinLimit) {
-          __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          break;
-        }
-      }
+      const int prev = __hip_atomic_fetch_add(&a.cnt[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_last = (prev == nparts - 1);
     }
     __syncthreads();
-    PKV_T(2);
-    PKV_TN(3);
-    {
-      // The statistics were written by other workgroups: read them with device-scope atomic loads, which
-      // cannot be served from a stale line, instead of invalidating caches.
+    if (s_last) {
       // NQ threads per row, each folds every NQ-th part (8 independent loads in flight), then they meet in LDS
       constexpr int NQ = kThreads / kRowBlock;
       const int q = tid >> 7, rl = tid & 127;
@@ -355,9 +397,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
               const int p = p0 + NQ * k;
               v[k] = make_float2(-INFINITY, 0.f);
               if (p < nparts) {
-                const unsigned long long bits = __hip_atomic_load(
-                    reinterpret_cast<const unsigned long long*>(a.part + ((size_t)u * a.TPU + p) * a.Rpad + r),
-                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const u64 bits = ld64(reinterpret_cast<const u64*>(part_base + (size_t)p * a.Rpad + r));
                 v[k] = make_float2(__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32)));
               }
             }
@@ -370,82 +410,122 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         if (q == 0) {
 #pragma unroll
           for (int k = 1; k < NQ; ++k) merge_stats(m, z, red[k][rl].x, red[k][rl].y);
-          // stored as -c_r/kappa (see sweep 2); padding rows get -inf and contribute exp2(-inf) = 0
-          cst[r] = (r < a.R) ? -(m + fast_log2(z)) * a.inv_kappa : -INFINITY;
+          // kept as -c_r/kappa (see sweep 2); padding rows get -inf and contribute exp2(-inf) = 0
+          const float c = (r < a.R) ? -(m + fast_log2(z)) * a.inv_kappa : -INFINITY;
+          cst[r] = c;
+          if (r < a.R) st64(&cbuf[r], ((u64)tag << 32) | __float_as_uint(c));
         }
         __syncthreads();
       }
+    } else {
+      for (int r = tid; r < a.Rpad; r += kThreads) {
+        float c = -INFINITY;
+        if (r < a.R) {
+          int spins = 0;
+          u64 w;
+          for (;;) {
+            w = ld64(&cbuf[r]);
+            if ((unsigned)(w >> 32) == tag) break;
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > kSpinLimit || ((spins & 1023) == 0 && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+              __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              break;
+            }
+          }
+          c = __uint_as_float((unsigned)w);
+        }
+        cst[r] = c;
+      }
+      __syncthreads();
     }
-
-    PKV_T(3);
+    PKV_T(2);
     PKV_TN(4);
+
     // ---- 4. sweep 2: normalised probabilities summed over the query rows ----
-    // Here the product's rows are query rows (lane holds rows 4*kq..+3 of the sub-tile) and its columns
-    // keys (lane & 15).  cst[] holds -c_r/kappa and is the initial accumulator of each product, so the
-    // product comes out as (q.k - c_r/kappa) and one multiply + exp2 per logit remain.
-    float e[kTilesPerWave][2];
+    // Here the product's rows are query rows (element v of a lane: row mrow0(v) + 4*hf of the tile) and its
+    // columns keys (lane & 31).  cst[] holds -c_r/kappa and is the initial accumulator of each product, so the
+    // product comes out as (q.k - c_r/kappa) and one multiply + exp2 + add per logit remain.
+    float e[kTiles];
 #pragma unroll
-    for (int t = 0; t < kTilesPerWave; ++t) e[t][0] = e[t][1] = 0.f;
+    for (int t = 0; t < kTiles; ++t) e[t] = 0.f;
     for (int rb = 0; rb < a.nrb; ++rb) {
       if (a.nrb > 1) {
-        stage_q(rb);
+        u32x4 qv[QLD];
+        __syncthreads();
+        stage_q_issue(rb, qv);
+        stage_q_commit(qv);
         __syncthreads();
       }
       const int rows_here = min(kRowBlock, a.R - rb * kRowBlock);
       const int nrt = (rows_here + 31) / 32;
-      bf16x8 qf[NF];
-      f32x4 cinit[2];
+      if (has_keys) {
+        bf16x8 qf[KS];
+        f32x16 cinit, cur, nxt;
+        auto load_cinit = [&](int rt, int j) {
+          const f32x4 c = *reinterpret_cast<const f32x4*>(&cst[rb * kRowBlock + 32 * rt + 8 * j + 4 * hf]);
+          cinit[4 * j + 0] = c[0]; cinit[4 * j + 1] = c[1]; cinit[4 * j + 2] = c[2]; cinit[4 * j + 3] = c[3];
+        };
 #pragma unroll
-      for (int ms = 0; ms < 2; ++ms) {
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = q_frag(0, ks);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ms * KS + ks] = as_frag(qs[lds_slot<SEG>(16 * ms + l16, 4 * ks + kq)]);
-        cinit[ms] = *reinterpret_cast<const f32x4*>(&cst[rb * kRowBlock + 16 * ms + 4 * kq]);
-      }
-      f32x4 acc_cur = cinit[0], acc_nxt;
+        for (int j = 0; j < 4; ++j) load_cinit(0, j);
+        cur = cinit;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) acc_cur = PKV_MFMA16(qf[ks], kf[0][ks], acc_cur);
+        for (int ks = 0; ks < KS; ++ks) cur = PKV_MFMA32(qf[ks], kf[0][ks], cur);
 #pragma unroll 1
-      for (int rt = 0; rt < nrt; ++rt) {
-        const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;
+        for (int rt = 0; rt < nrt; ++rt) {
+          const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;
 #pragma unroll
-        for (int i = 0; i < NSUB; ++i) {
-          const int t = i >> 2, ns = (i >> 1) & 1;
-          const int j = (i + 1) % NSUB, tj = j >> 2, nsj = (j >> 1) & 1, msj = j & 1;
-          if (i >= NSUB - 2) {  // this half tile's Q fragments and normalisers are free: fetch the next row tile's
+          for (int t = 0; t < kTiles; ++t) {
+            const int tn = (t + 1) % kTiles;
+            float s0 = 0.f, s1 = 0.f;
+            nxt = cinit;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-              qf[(i & 1) * KS + ks] = as_frag(qs[lds_slot<SEG>(32 * rt_next + 16 * (i & 1) + l16, 4 * ks + kq)]);
-            cinit[i & 1] = *reinterpret_cast<const f32x4*>(&cst[rb * kRowBlock + 32 * rt_next + 16 * (i & 1) + 4 * kq]);
+            for (int ks = 0; ks < KS; ++ks) {
+              nxt = PKV_MFMA32(qf[ks], kf[tn][ks], nxt);
+              if (t == kTiles - 2) {  // this row tile's fragments and normalisers are free: fetch the next tile's
+                qf[ks] = q_frag(rt_next, ks);
+                if (ks < 4) load_cinit(rt_next, ks);
+              }
+              float x[TPM], ee[TPM];
+#pragma unroll
+              for (int j = 0; j < TPM; ++j) x[j] = cur[TPM * ks + j] * a.kappa;
+#pragma unroll
+              for (int j = 0; j < TPM; ++j) ee[j] = fast_exp2(x[j]);
+#pragma unroll
+              for (int j = 0; j < TPM; ++j) {
+                if (j & 1) s1 += ee[j]; else s0 += ee[j];
+              }
+              PKV_SG_MFMA(1);
+              if (t == kTiles - 2) {
+                if (ks < 4) PKV_SG_DSR(2); else PKV_SG_DSR(1);
+              }
+              PKV_SG_VALU(TPM);
+              PKV_SG_TRANS(TPM);
+              PKV_SG_VALU(TPM);
+            }
+            e[t] += s0 + s1;
+            cur = nxt;
           }
-          acc_nxt = cinit[msj];
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) acc_nxt = PKV_MFMA16(qf[msj * KS + ks], kf[tj][nsj * KS + ks], acc_nxt);
-          const float e0 = fast_exp2(acc_cur[0] * a.kappa), e1 = fast_exp2(acc_cur[1] * a.kappa);
-          const float e2 = fast_exp2(acc_cur[2] * a.kappa), e3 = fast_exp2(acc_cur[3] * a.kappa);
-          e[t][ns] += (e0 + e1) + (e2 + e3);
-          acc_cur = acc_nxt;
         }
       }
-      if (a.nrb > 1) __syncthreads();
     }
-    float* raw = a.raw + (size_t)u * a.N;
+    if (has_keys) {
+      float* raw = a.raw + (size_t)u * a.N;
 #pragma unroll
-    for (int t = 0; t < kTilesPerWave; ++t)
-#pragma unroll
-      for (int ns = 0; ns < 2; ++ns) {
-        float tot = e[t][ns];
-        tot += __shfl_xor(tot, 16);
+      for (int t = 0; t < kTiles; ++t) {
+        float tot = e[t];
         tot += __shfl_xor(tot, 32);
-        const int key = wkey0 + 32 * t + 16 * ns + l16;
-        if (kq == 0 && key < npre) raw[key] = tot * a.inv_G;
+        const int key = wkey0 + 32 * t + l32;
+        if (hf == 0 && key < npre) raw[key] = tot * a.inv_G;
       }
-    __syncthreads();  // cst / qs / red are reused by the next round
-    first = false;
+    }
+    __syncthreads();  // cst / qs / red are reused by the next unit
     PKV_T(4);
   }
-  // a set-0 workgroup that never reached a barrier must not leave set 1 waiting
-  if (set == 0 && tid == 0) __hip_atomic_store(a.go, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #ifdef PKV_RES_TIMING
+  tstamp[5] += clock64();
+  tstamp[6] += wall_clock64();
   if (tid == 0 && a.dbg)
     for (int i = 0; i < 8; ++i) a.dbg[blockIdx.x * 8 + i] = tstamp[i];
 #endif
@@ -459,8 +539,8 @@ __global__ void zero_kernel(int32_t* p, int n) {
 }  // namespace
 
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s) {
-  // the counters (and the error and go words behind them) must start at zero
-  const int nz = a.U + 2;
+  // the counters, the error word and the tagged normaliser words must start at zero
+  const int nz = a.sync_words;
   hipLaunchKernelGGL(zero_kernel, dim3((nz + 255) / 256), dim3(256), 0, s, a.cnt, nz);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -141,10 +141,10 @@ static bool device_fits_resident() {
   return cached[dev] == 1;
 }
 
-// Late start of the second workgroup of each compute unit, in 10 ns ticks (tuning hook: PKV_STAGGER).
+// Start offset between consecutive workgroup groups, in 10 ns ticks (tuning hook: PKV_STAGGER).
 static int resident_stagger() {
   if (const char* e = getenv("PKV_STAGGER")) return atoi(e);
-  return 500;
+  return 250;
 }
 
 static bool use_resident(const Plan& plan) {

@@ -62,7 +62,7 @@ struct ScoreArgs {
 constexpr int kResidentCUs = 256;       // compute units the persistent grid is sized for
 constexpr int kResidentGrid = 512;      // persistent workgroups: two per compute unit, one wave per SIMD each
 constexpr int kResidentKeys = 512;      // keys held in registers by one workgroup (4 waves x 4 tiles x 32)
-constexpr int kResidentMaxRows = 1024;  // G * alpha (padded to 128) the LDS normaliser table can hold
+constexpr int kResidentMaxRows = 512;   // G * alpha (padded to 128) the LDS normaliser table can hold
 constexpr int kResidentMaxLayers = 96;  // per launch (kernel-argument table)
 
 struct ResidentLayer {
@@ -85,7 +85,7 @@ struct ResidentArgs {
   int32_t L, B, Hq, Hkv, G, alpha, N, R, Rpad, nrb, TPU, U, d;
   int32_t ngroups;  // independent groups of workgroups: 512 / group size
   int32_t UPG;      // units a group works on at the same time: group size / TPU
-  int32_t stagger;  // late start of the second workgroup of each compute unit, in 10 ns ticks
+  int32_t stagger;  // start offset between consecutive groups, in 10 ns ticks
   int64_t q_sb, q_sh, q_st, kv_sb, kv_sh, kv_st;
   float kappa, inv_kappa, inv_G;
 };

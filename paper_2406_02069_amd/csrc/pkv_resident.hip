@@ -39,6 +39,8 @@
 // Every wait is bounded: a workgroup that spins too long raises the error word and carries on, so the
 // grid always drains.  The launch uses exactly 512 workgroups, two per compute unit (register- and
 // LDS-limited), which the host checks against the device before choosing this path.
+#include <type_traits>
+
 #include "pkv_internal.h"
 
 namespace pkv {
@@ -61,23 +63,49 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 __device__ __forceinline__ bf16x8 as_frag(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 #define PKV_MFMA32(A, B, C) __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, C, 0, 0, 0)
-// scheduling groups: the next N instructions of a class, in this order
-#define PKV_SG_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
-#define PKV_SG_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
-#define PKV_SG_TRANS(n) __builtin_amdgcn_sched_group_barrier(0x400, n, 0)
-#define PKV_SG_DSR(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
+// End of a hand-ordered chunk (one MFMA, the exponentials that run in its shadow, at most one LDS read):
+// nothing is scheduled across this point, so the interleaving written in the source is what is emitted.
+#define PKV_CHUNK_END() __builtin_amdgcn_sched_barrier(0)
+// The same, and the two running sums are pinned here: without that the optimiser sinks the exponentials of
+// all chunks to the place where the sums are finally used, behind the last MFMA.
+#define PKV_CHUNK_END_SUMS(s0, s1)                 \
+  do {                                             \
+    asm volatile("" : "+v"(s0), "+v"(s1));         \
+    __builtin_amdgcn_sched_barrier(0);             \
+  } while (0)
 
 // The Q block is kept in LDS with a row pitch of SEG + 1 sixteen-byte segments: consecutive rows then
 // start 4 banks apart (mod 64), so the 16 rows that one ds_read_b128 phase touches hit all banks once,
 // and the segment index stays a compile-time address offset.
 template <int SEG>
-__device__ __forceinline__ constexpr int lds_pitch() { return SEG + 1; }
+__host__ __device__ __forceinline__ constexpr int lds_pitch() { return SEG + 1; }
 
 __device__ __forceinline__ void merge_stats(float& m, float& z, float m2, float z2) {
   const float M = fmaxf(m, m2);
   const float Ms = (M == -INFINITY) ? 0.f : M;
   z = z * fast_exp2(m - Ms) + z2 * fast_exp2(m2 - Ms);
   m = M;
+}
+
+// -c/kappa as three bf16 summands (hi + mid + lo reproduces the fp32 value to 2^-24): the layout of the
+// first three k-elements of an MFMA operand.  -inf stays -inf (padding rows).
+__device__ __forceinline__ u64 split3(float c) {
+  const __bf16 hi = (__bf16)c;
+  float r = c - (float)hi;
+  if (c == -INFINITY) r = 0.f;
+  const __bf16 mid = (__bf16)r;
+  r -= (float)mid;
+  const __bf16 lo = (__bf16)r;
+  const uint32_t w0 = (uint32_t)__builtin_bit_cast(uint16_t, hi) | ((uint32_t)__builtin_bit_cast(uint16_t, mid) << 16);
+  const uint32_t w1 = (uint32_t)__builtin_bit_cast(uint16_t, lo);
+  return ((u64)w1 << 32) | w0;
+}
+
+// A value the compiler must treat as new: lane constants derived from it are recomputed where they are
+// used instead of being kept (and spilled) across the whole unit loop.
+__device__ __forceinline__ int fresh(int v) {
+  asm volatile("" : "+v"(v));
+  return v;
 }
 
 __device__ __forceinline__ void st64(u64* p, u64 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -94,17 +122,21 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   constexpr int PITCH = lds_pitch<SEG>();
   constexpr int QLD = kRowBlock * SEG / kThreads;  // 16-byte loads per thread for one block of Q
   constexpr int RPP = kThreads / SEG;              // rows covered by one pass of the workgroup
-  __shared__ u32x4 qs[kRowBlock * PITCH];        // current 128-row block of Q
-  __shared__ float2 red[kWaves][kRowBlock];
-  __shared__ __attribute__((aligned(16))) float cst[kResidentMaxRows];
-  __shared__ int qoff[kRowBlock];
-  __shared__ int s_last;
+  constexpr int QBUF = kRowBlock * PITCH;          // 16-byte slots of one Q buffer
+  extern __shared__ u32x4 qsmem[];                 // two buffers for 128-row blocks of Q
+  // sweep-1 statistics per wave, wave half and row.  Between sweeps the same memory serves as scratch for
+  // the fold, as the row-offset table of the Q staging and as the "last to arrive" flag (never at once).
+  __shared__ float2 stat_mem[kWaves * 2 * kRowBlock];
+  // per-row normalisers, ready for the matrix pipe: -c_r/kappa split into three bf16 (hi | mid << 16, lo)
+  __shared__ u64 cfr[kResidentMaxRows];
+  float2 (*stat)[2][kRowBlock] = reinterpret_cast<float2 (*)[2][kRowBlock]>(stat_mem);
+  int* qoff = reinterpret_cast<int*>(stat_mem);                                  // [kRowBlock]
+  int* s_last_p = reinterpret_cast<int*>(stat_mem + kWaves * 2 * kRowBlock) - 1;  // last word
+#define s_last (*s_last_p)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps addressing in scalar registers
-  const int l32 = lane & 31;
-  const int hf = lane >> 5;
   const int BH = a.B * a.Hkv;
 
   // ---- which group, which slot ----
@@ -129,122 +161,173 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   const int nslots = a.ngroups * a.UPG;
   float2* part_base = a.part + (size_t)slot_id * a.TPU * a.Rpad;
   u64* cbuf = a.cbuf + (size_t)slot_id * a.Rpad;
+  const int key0 = part_id * kResidentKeys;
+  const int wkey0 = key0 + wave * (kTiles * 32);
 
 #ifdef PKV_RES_TIMING
   long long tstamp[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   tstamp[5] = -(long long)clock64();
   tstamp[6] = -(long long)wall_clock64();
-  // absolute phase-boundary times of a few workgroups (the two of one compute unit, on two XCDs)
-  const int trace_id = (blockIdx.x == 0) ? 0 : (blockIdx.x == 256) ? 1 : (blockIdx.x == 1) ? 2 : (blockIdx.x == 257) ? 3 : -1;
+  // absolute phase-boundary times of one workgroup of every group: blocks 0,2,4,6 and 256,258,260,262
+  const int trace_id = ((blockIdx.x & ~0x106) == 0 && (blockIdx.x & 1) == 0) ? (int)((blockIdx.x >> 8) * 4 + ((blockIdx.x & 6) >> 1)) : -1;
   int trace_n = 0;
-#define PKV_TRACE() do { if (trace_id >= 0 && trace_n < 240 && tid == 0 && a.dbg) a.dbg[kResidentGrid * 8 + trace_id * 256 + trace_n] = wall_clock64(); ++trace_n; } while (0)
-#define PKV_T(i) do { tstamp[i] += wall_clock64(); PKV_TRACE(); } while (0)
-#define PKV_TN(i) do { tstamp[i] -= wall_clock64(); if (i == 0) PKV_TRACE(); } while (0)
+#define PKV_TRACE() do { if (trace_id >= 0 && trace_n < 128 && tid == 0 && a.dbg) a.dbg[kResidentGrid * 8 + trace_id * 128 + trace_n] = wall_clock64(); ++trace_n; } while (0)
+#define PKV_T(i) do { tstamp[i] += wall_clock64(); if (i != 0) PKV_TRACE(); } while (0)
+#define PKV_TN(i) do { tstamp[i] -= wall_clock64(); if (i == 1) PKV_TRACE(); } while (0)
+  if (set == 1 && a.stagger < 0) return;  // measurement: one workgroup per compute unit
 #else
 #define PKV_T(i)
 #define PKV_TN(i)
 #endif
 
-#ifdef PKV_RES_TIMING
-  if (set == 1 && a.stagger < 0) return;  // measurement: one workgroup per compute unit
-#endif
-  if (set == 1 && a.stagger > 0) {  // late start of the second set: a plain timed wait
-    const long long t0 = wall_clock64();
-    while (wall_clock64() - t0 < a.stagger) __builtin_amdgcn_s_sleep(16);
+  if (a.stagger > 0 && a.ngroups >= 2) {
+    // Staggered start (a plain timed wait): the groups begin evenly spread over one period, the two
+    // groups that share compute units half a period apart.
+    const int rank = (group >> 1) + (a.ngroups >> 1) * set;
+    const long long t0 = wall_clock64(), wait = (long long)a.stagger * rank;
+    while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);
   }
 
-  for (int u = slot_id; u < a.U; u += nslots) {
-    const int l = u / BH;
-    const int bg = u - l * BH;
-    const int b = bg / a.Hkv;
-    const int g = bg - b * a.Hkv;
-    int n = a.N;
-    if (a.seq_lens) {
-      n = a.seq_lens[b];
-      n = n < 0 ? 0 : (n > a.N ? a.N : n);
+  // One unit as this workgroup sees it (all fields wave-uniform).
+  struct Unit {
+    int u, n, npre, nparts;
+    const uint16_t* Q;
+    const uint16_t* K;
+  };
+  // First unit at or after `u` (in steps of nslots) in which this workgroup has keys to score.
+  auto find_unit = [&](int u, Unit& d) {
+    for (; u < a.U; u += nslots) {
+      const int l = u / BH;
+      const int bg = u - l * BH;
+      const int b = bg / a.Hkv;
+      const int g = bg - b * a.Hkv;
+      int n = a.N;
+      if (a.seq_lens) {
+        n = a.seq_lens[b];
+        n = n < 0 ? 0 : (n > a.N ? a.N : n);
+      }
+      if (a.layer[l].k_l >= n) continue;  // whole sequence kept: no scores needed (uniform over the unit)
+      if (key0 >= n) continue;            // no keys here; this part is not counted at the barrier
+      d.u = u;
+      d.n = n;
+      d.npre = n - a.alpha;
+      d.nparts = (n + kResidentKeys - 1) / kResidentKeys;
+      d.Q = a.layer[l].Q + (size_t)b * a.q_sb + (size_t)(g * a.G) * a.q_sh;
+      d.K = a.layer[l].K + (size_t)b * a.kv_sb + (size_t)g * a.kv_sh;
+      return;
     }
-    if (a.layer[l].k_l >= n) continue;  // whole sequence kept: no scores needed (uniform over the unit)
-    const int key0 = part_id * kResidentKeys;
-    if (key0 >= n) continue;            // no keys here; this part is not counted below
-    const int nparts = (n + kResidentKeys - 1) / kResidentKeys;
-    const int npre = n - a.alpha;
-    const int wkey0 = key0 + wave * (kTiles * 32);
+    d.u = a.U;
+  };
+
+  // Stage a 128-row block of Q in LDS.  qoff[row] = byte offset of the row (-1: padding row).
+  // Thread -> (row tid / SEG + RPP * i, segment tid % SEG): 16 bytes per load, rows fully coalesced.
+  // Callers put a workgroup barrier between this and the first read of the buffer.
+  auto stage_q = [&](const Unit& d, int rb, u32x4* qb) {
+    const int tid_ = fresh(tid);
+    const int q_row0 = tid_ / SEG, q_seg = tid_ - q_row0 * SEG;
+    if (tid < kRowBlock) {
+      const int r = rb * kRowBlock + tid;
+      int off = -1;
+      if (r < a.R) {
+        const int hh = r / a.alpha, t = r - hh * a.alpha;
+        off = (int)(hh * a.q_sh + t * a.q_st) * 2;
+      }
+      qoff[tid] = off;
+    }
+    __syncthreads();
+    const char* src = reinterpret_cast<const char*>(d.Q) + q_seg * 16;
+    u32x4 v[QLD];
+#pragma unroll
+    for (int i = 0; i < QLD; ++i) {
+      const int off = qoff[q_row0 + RPP * i];
+      v[i] = u32x4{0u, 0u, 0u, 0u};
+      if (off >= 0) v[i] = *reinterpret_cast<const u32x4*>(src + (uint32_t)off);
+    }
+    u32x4* dst = qb + q_row0 * PITCH + q_seg;
+#pragma unroll
+    for (int i = 0; i < QLD; ++i) dst[RPP * i * PITCH] = v[i];
+  };
+
+  // The wave's keys as MFMA operand fragments: kf[t][ks] = for key 32*t + (lane & 31), the 8 elements at
+  // 16*ks + 8*(lane >> 5).  Loaded straight from global memory in this layout.
+  bf16x8 kf[kTiles][KS];
+  // Request fragments [KLO, KHI) of key tile T of unit d.  Branch-free: keys at or beyond n are clamped to the
+  // last valid row (never read beyond it); a wave without keys in that unit just fetches that row.
+  auto issue_k = [&](const Unit& d, auto T, auto KLO, auto KHI) {
+    constexpr int t = decltype(T)::value;
+    const int lane_ = fresh(lane);
+    const int l32 = lane_ & 31, hf = lane_ >> 5;
+    const int key = min(wkey0 + 32 * t + l32, d.n - 1);
+    // 32-bit byte offsets from the head's first key (the host admits only shapes where they fit)
+    const char* rowp = reinterpret_cast<const char*>(d.K) + 16 * hf + (uint32_t)key * ((uint32_t)a.kv_st * 2u);
+#pragma unroll
+    for (int ks = decltype(KLO)::value; ks < decltype(KHI)::value; ++ks)
+      kf[t][ks] = as_frag(*reinterpret_cast<const u32x4*>(rowp + 32 * ks));
+  };
+  using IKS = std::integral_constant<int, KS>;
+  using IKH = std::integral_constant<int, KS / 2>;
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+  using INONE = std::integral_constant<int, -1>;
+  // While a pass works on one pair of key tiles, the other pair can be refilled: half a tile (RFT, or none if
+  // negative) after the middle chunk of a step, at fixed places of the first two row-tile iterations, so that
+  // the loads trickle out in the shadow of the arithmetic instead of stalling the wave at the memory
+  // pipeline's entrance.  (Unconditional loads at fixed places: loads under a run-time condition keep the
+  // old and the new fragments alive side by side, which the register budget cannot afford.)
+  auto refill = [&](const Unit& ru, auto RFT, auto HALF) {
+    if constexpr (decltype(RFT)::value >= 0) {
+      using LO = std::integral_constant<int, decltype(HALF)::value * (KS / 2)>;
+      using HI = std::integral_constant<int, decltype(HALF)::value * (KS / 2) + KS / 2>;
+      issue_k(ru, RFT, LO{}, HI{});
+      PKV_CHUNK_END();
+    }
+  };
+
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  if (tid == 0) qsmem[SEG] = u32x4{0u, 0u, 0u, 0u};  // pad slot of row 0: never written by the staging
+  Unit cur_u, nxt_u;
+  find_unit(slot_id, cur_u);
+  if (cur_u.u >= a.U) return;
+  int buf = 0;
+  PKV_TN(0);
+  stage_q(cur_u, 0, qsmem);
+  issue_k(cur_u, I0{}, I0{}, IKS{});
+  issue_k(cur_u, I1{}, I0{}, IKS{});
+  issue_k(cur_u, I2{}, I0{}, IKS{});
+  issue_k(cur_u, I3{}, I0{}, IKS{});
+  __syncthreads();
+  PKV_T(0);
+
+  while (cur_u.u < a.U) {
+    const int u = cur_u.u, n = cur_u.n, npre = cur_u.npre, nparts = cur_u.nparts;
+    find_unit(u + nslots, nxt_u);
+    const bool has_next = nxt_u.u < a.U;
     const bool has_keys = wkey0 < n;                      // wave-uniform
-    const bool whole = wkey0 + kTiles * 32 <= n;
     // tile t needs masks iff it reaches beyond the prefix (causal window, end of the sequence)
     int dirty_mask = 0;
 #pragma unroll
     for (int t = 0; t < kTiles; ++t) dirty_mask |= (wkey0 + 32 * t + 32 > npre) ? (1 << t) : 0;
-    const uint16_t* Qbase = a.layer[l].Q + (size_t)b * a.q_sb + (size_t)(g * a.G) * a.q_sh;
-    const uint16_t* Kbase = a.layer[l].K + (size_t)b * a.kv_sb + (size_t)g * a.kv_sh;
-
-    // Stage a 128-row block of Q in LDS.  qoff[row] = byte offset of the row (-1: padding row).
-    // Thread -> (row tid / SEG + RPP * i, segment tid % SEG): 16 bytes per load, rows fully coalesced.
-    const int q_row0 = tid / SEG, q_seg = tid - q_row0 * SEG;
-    auto stage_q_issue = [&](int rb, u32x4 (&v)[QLD]) {
-      if (tid < kRowBlock) {
-        const int r = rb * kRowBlock + tid;
-        int off = -1;
-        if (r < a.R) {
-          const int hh = r / a.alpha, t = r - hh * a.alpha;
-          off = (int)(hh * a.q_sh + t * a.q_st) * 2;
-        }
-        qoff[tid] = off;
-      }
-      __syncthreads();
-      const char* qb = reinterpret_cast<const char*>(Qbase) + q_seg * 16;
-#pragma unroll
-      for (int i = 0; i < QLD; ++i) {
-        const int off = qoff[q_row0 + RPP * i];
-        v[i] = u32x4{0u, 0u, 0u, 0u};
-        if (off >= 0) v[i] = *reinterpret_cast<const u32x4*>(qb + (uint32_t)off);
-      }
-    };
-    auto stage_q_commit = [&](const u32x4 (&v)[QLD]) {
-      u32x4* dst = qs + q_row0 * PITCH + q_seg;
-#pragma unroll
-      for (int i = 0; i < QLD; ++i) dst[RPP * i * PITCH] = v[i];
-    };
-
-    // ---- 1. Q block 0 -> LDS, keys -> registers (fragment layout, no staging) ----
-    PKV_TN(0);
-    bf16x8 kf[kTiles][KS];
-    {
-      u32x4 qv[QLD];
-      stage_q_issue(0, qv);  // issued first: loads return in order, and the Q block is needed first
-      if (has_keys) {
-        // 32-bit byte offsets from the head's first key (the host admits only shapes where they fit)
-        const char* kb = reinterpret_cast<const char*>(Kbase) + 16 * hf;
-        const uint32_t row_bytes = (uint32_t)a.kv_st * 2u;
-#pragma unroll
-        for (int t = 0; t < kTiles; ++t) {
-          int key = wkey0 + 32 * t + l32;
-          if (!whole) key = min(key, n - 1);  // rows at or beyond n are never read
-          const char* rowp = kb + (uint32_t)key * row_bytes;
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) kf[t][ks] = as_frag(*reinterpret_cast<const u32x4*>(rowp + 32 * ks));
-        }
-      }
-      stage_q_commit(qv);
-    }
-    __syncthreads();
-    PKV_T(0);
-    PKV_TN(1);
-
+    u32x4* qb = qsmem + buf * QBUF;
+    const int lane_u = fresh(lane);
+    const int l32 = lane_u & 31, hf = lane_u >> 5;
+    const u32x4* q_lane = qb + l32 * PITCH + hf;
     // LDS reads of one 32-row tile of Q as MFMA operand fragments
-    const u32x4* q_lane = qs + l32 * PITCH + hf;
     auto q_frag = [&](int rt, int ks) { return as_frag(q_lane[32 * rt * PITCH + 2 * ks]); };
 
-    // ---- 2. sweep 1: per-row statistics over this workgroup's keys ----
+    PKV_TN(1);
+    // ---- sweep 1: per-row statistics over this workgroup's keys ----
     // Products: rows = keys (element v of a lane: key mrow0(v) + 4*hf of the tile), columns = query rows
-    // (lane & 31).  Per lane and row tile: reference exponent m (log2 domain) and z = sum exp2(x - m).
+    // (lane & 31).  Per lane and row tile: reference exponent m (log2 domain) and z = sum exp2(x - m), kept in
+    // LDS between the two passes over the row tiles (first the tiles 0,1 of the keys, then 2,3: the second
+    // half of the keys may still be in flight during the first pass).
     float2* part = part_base + (size_t)part_id * a.Rpad;
     for (int rb = 0; rb < a.nrb; ++rb) {
       if (rb > 0) {
-        u32x4 qv[QLD];
         __syncthreads();  // everyone is done with the previous block
-        stage_q_issue(rb, qv);
-        stage_q_commit(qv);
+        stage_q(cur_u, rb, qb);
         __syncthreads();
       }
       const int rows_here = min(kRowBlock, a.R - rb * kRowBlock);
@@ -268,11 +351,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
           z = z * fast_exp2(m - ms) + s;
           m = mn;
         };
-        auto finish_rt = [&](int rt, float m, float z) {
-          const float m2 = __shfl_xor(m, 32), z2 = __shfl_xor(z, 32);
-          merge_stats(m, z, m2, z2);
-          if (hf == 0) red[wave][32 * rt + l32] = make_float2(m, z);
-        };
         // last key (relative to this wave's first key and half) that the lane's query of row tile rt sees
         auto lim_rel_of = [&](int rt) {
           const int r = rb * kRowBlock + 32 * rt + l32;
@@ -282,66 +360,88 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
 
         bf16x8 qf[KS];
         f32x16 cur, nxt;
-        const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = q_frag(0, ks);
-        cur = zero16;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) cur = PKV_MFMA32(kf[0][ks], qf[ks], cur);
         int redo = 0;  // row tiles whose provisional reference failed (wave-uniform bit mask)
-#pragma unroll 1
-        for (int rt = 0; rt < nrt; ++rt) {
+        // One step of the pipeline: issue the MFMAs of the product (TN, current qf) and meanwhile turn the
+        // finished product `cur` of tile TC into exponentials.  RELOAD: the issued product is the last use
+        // of qf, which is refilled for row tile rt_next as the MFMAs go out.
+        auto step = [&](auto TC, auto TN, auto FIRST, auto RELOAD, auto RFT, auto HALF, const Unit& ru, int rt,
+                        int rt_next, float& m, float& z) {
+          constexpr int tc = decltype(TC)::value, tn = decltype(TN)::value;
+          if (dirty_mask & (1 << tc)) {
+            // slow variant (masks, exact update); the next product is still issued first
+            nxt = zero16;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+              nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
+              if (decltype(RELOAD)::value) qf[ks] = q_frag(rt_next, ks);
+            }
+            refill(ru, RFT, HALF);
+            exact_update(cur, tc, true, lim_rel_of(rt), m, z);
+          } else {
+            if (decltype(FIRST)::value) {  // provisional reference: the largest of three of the lane's logits
+              m = a.kappa * fmaxf(fmaxf(cur[0], cur[5]), cur[10]);
+              z = 0.f;
+            }
+            const float nref = -m;
+            float s0 = 0.f, s1 = 0.f;
+            nxt = zero16;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+              nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
+              if (decltype(RELOAD)::value) qf[ks] = q_frag(rt_next, ks);  // last use of this fragment was the MFMA above
+              float x[TPM], e[TPM];
+#pragma unroll
+              for (int j = 0; j < TPM; ++j) x[j] = __builtin_fmaf(cur[TPM * ks + j], a.kappa, nref);
+#pragma unroll
+              for (int j = 0; j < TPM; ++j) e[j] = fast_exp2(x[j]);
+#pragma unroll
+              for (int j = 0; j < TPM; ++j) {
+                if (j & 1) s1 += e[j]; else s0 += e[j];
+              }
+              PKV_CHUNK_END_SUMS(s0, s1);
+              if (ks == KS / 2 - 1) refill(ru, RFT, HALF);
+            }
+            z += s0 + s1;
+          }
+          cur = nxt;
+        };
+        using F = std::false_type;
+        using T = std::true_type;
+        // both products of one row tile with the key tiles (TA, TB); RFT: key tile refilled meanwhile
+        auto iter = [&](auto TA, auto TB, auto FIRSTPASS, auto RFT, const Unit& ru, int rt) {
           const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;  // after the last tile one unused product is issued
           float m = -INFINITY, z = 0.f;  // m: reference exponent of this lane (not necessarily the maximum)
-          const int lim_rel = lim_rel_of(rt);
-#pragma unroll
-          for (int t = 0; t < kTiles; ++t) {
-            const int tn = (t + 1) % kTiles;
-            if (dirty_mask & (1 << t)) {
-              // slow variant of the step (masks, exact update); the next product is still issued first
-              nxt = zero16;
-#pragma unroll
-              for (int ks = 0; ks < KS; ++ks) {
-                nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
-                if (t == kTiles - 2) qf[ks] = q_frag(rt_next, ks);
-              }
-              exact_update(cur, t, true, lim_rel, m, z);
-            } else {
-              float nref;
-              if (t == 0) {  // provisional reference: the largest of three of the lane's logits
-                m = a.kappa * fmaxf(fmaxf(cur[0], cur[5]), cur[10]);
-                z = 0.f;
-              }
-              nref = -m;
-              float s0 = 0.f, s1 = 0.f;
-              nxt = zero16;
-#pragma unroll
-              for (int ks = 0; ks < KS; ++ks) {
-                nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
-                if (t == kTiles - 2) qf[ks] = q_frag(rt_next, ks);  // last use of this fragment was the MFMA above
-                float x[TPM], e[TPM];
-#pragma unroll
-                for (int j = 0; j < TPM; ++j) x[j] = __builtin_fmaf(cur[TPM * ks + j], a.kappa, nref);
-#pragma unroll
-                for (int j = 0; j < TPM; ++j) e[j] = fast_exp2(x[j]);
-#pragma unroll
-                for (int j = 0; j < TPM; ++j) {
-                  if (j & 1) s1 += e[j]; else s0 += e[j];
-                }
-                PKV_SG_MFMA(1);
-                if (t == kTiles - 2) PKV_SG_DSR(1);
-                PKV_SG_VALU(TPM);
-                PKV_SG_TRANS(TPM);
-                PKV_SG_VALU(TPM);
-              }
-              z += s0 + s1;
-            }
-            cur = nxt;
+          if (!decltype(FIRSTPASS)::value) {
+            const float2 st = stat[wave][hf][32 * rt + l32];
+            m = st.x;
+            z = st.y;
           }
+          step(TA, TB, FIRSTPASS, T{}, RFT, I0{}, ru, rt, rt_next, m, z);
+          step(TB, TA, F{}, F{}, RFT, I1{}, ru, rt, rt_next, m, z);
+          stat[wave][hf][32 * rt + l32] = make_float2(m, z);
           // a sum outside the safe range (or NaN) means the provisional reference was too far off
-          if (__any(!(z <= 0x1p100f))) redo |= 1 << rt;
-          finish_rt(rt, m, z);
-        }
+          if (!decltype(FIRSTPASS)::value && __any(!(z <= 0x1p100f))) redo |= 1 << rt;
+        };
+        // pass over the row tiles with the key tiles (TA, TB); REFILL: key tiles (F0, F1) are requested for ru
+        auto pass = [&](auto TA, auto TB, auto FIRSTPASS, auto REFILL, auto F0, auto F1, const Unit& ru) {
+          constexpr int ta = decltype(TA)::value;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) qf[ks] = q_frag(0, ks);
+          cur = zero16;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) cur = PKV_MFMA32(kf[ta][ks], qf[ks], cur);
+          int rt = 0;
+          if constexpr (decltype(REFILL)::value) {
+            iter(TA, TB, FIRSTPASS, F0, ru, 0);
+            if (nrt > 1) iter(TA, TB, FIRSTPASS, F1, ru, 1);
+            else issue_k(ru, F1, I0{}, IKS{});
+            rt = 2;
+          }
+#pragma unroll 1
+          for (; rt < nrt; ++rt) iter(TA, TB, FIRSTPASS, INONE{}, ru, rt);
+        };
+        pass(I0{}, I1{}, T{}, F{}, I2{}, I3{}, cur_u);
+        pass(I2{}, I3{}, F{}, F{}, I0{}, I1{}, cur_u);
         // rare: recompute flagged row tiles with the exact running-maximum update (pipeline is drained here)
         for (int rt = 0; redo != 0 && rt < nrt; ++rt) {
           if (!(redo & (1 << rt))) continue;
@@ -357,16 +457,19 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
             for (int ks = 0; ks < KS; ++ks) acc = PKV_MFMA32(kf[t][ks], q2[ks], acc);
             exact_update(acc, t, (dirty_mask >> t) & 1, lim_rel, m, z);
           }
-          finish_rt(rt, m, z);
+          stat[wave][hf][32 * rt + l32] = make_float2(m, z);
         }
       } else {
-        for (int r = lane; r < kRowBlock; r += 64) red[wave][r] = make_float2(-INFINITY, 0.f);
+        for (int r = lane; r < 2 * kRowBlock; r += 64) stat[wave][r >> 7][r & 127] = make_float2(-INFINITY, 0.f);
       }
       __syncthreads();
       if (tid < rows_here) {
-        float m = red[0][tid].x, z = red[0][tid].y;
+        float m = -INFINITY, z = 0.f;
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) merge_stats(m, z, red[w][tid].x, red[w][tid].y);
+        for (int w = 0; w < kWaves; ++w) {
+          merge_stats(m, z, stat[w][0][tid].x, stat[w][0][tid].y);
+          merge_stats(m, z, stat[w][1][tid].x, stat[w][1][tid].y);
+        }
         // device-scope store: written through, so that other XCDs see it without an L2 write-back
         st64(reinterpret_cast<u64*>(part + rb * kRowBlock + tid), ((u64)__float_as_uint(z) << 32) | __float_as_uint(m));
       }
@@ -375,49 +478,74 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     PKV_T(1);
     PKV_TN(2);
 
-    // ---- 3. arrive; the last part folds all parts into the per-row normaliser and publishes it ----
+    // ---- arrive; the last part folds all parts into the per-row normaliser and publishes it ----
     const unsigned tag = (unsigned)u + 1u;
     if (tid == 0) {
       const int prev = __hip_atomic_fetch_add(&a.cnt[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_last = (prev == nparts - 1);
     }
     __syncthreads();
-    if (s_last) {
-      // NQ threads per row, each folds every NQ-th part (8 independent loads in flight), then they meet in LDS
+    const bool last = s_last != 0;
+    bool q_staged = false;
+    if (last) {
+#ifdef PKV_RES_TIMING
+      tstamp[3] -= wall_clock64();
+      tstamp[7] += 1;
+#endif
+      // NQ threads per row, each folds every NQ-th part (32 independent loads in flight), then they meet in LDS
       constexpr int NQ = kThreads / kRowBlock;
+      constexpr int NLD = 32;
       const int q = tid >> 7, rl = tid & 127;
+      float2* red = &stat[0][0][0];  // [NQ][kRowBlock]
       for (int r0 = 0; r0 < a.Rpad; r0 += kRowBlock) {
         const int r = r0 + rl;
         float m = -INFINITY, z = 0.f;
         if (r < a.R) {
-          for (int p0 = q; p0 < nparts; p0 += 8 * NQ) {
-            float2 v[8];
+          for (int p0 = q; p0 < nparts; p0 += NLD * NQ) {
+            u64 bits[NLD];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-              const int p = p0 + NQ * k;
-              v[k] = make_float2(-INFINITY, 0.f);
-              if (p < nparts) {
-                const u64 bits = ld64(reinterpret_cast<const u64*>(part_base + (size_t)p * a.Rpad + r));
-                v[k] = make_float2(__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32)));
-              }
+            for (int k = 0; k < NLD; ++k) {
+              const int p = min(p0 + NQ * k, nparts - 1);  // clamped: duplicates are skipped below
+              bits[k] = ld64(reinterpret_cast<const u64*>(part_base + (size_t)p * a.Rpad + r));
             }
+            float M = m;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) merge_stats(m, z, v[k].x, v[k].y);
+            for (int k = 0; k < NLD; ++k)
+              if (p0 + NQ * k < nparts) M = fmaxf(M, __uint_as_float((uint32_t)bits[k]));
+            const float Ms = (M == -INFINITY) ? 0.f : M;
+            z *= fast_exp2(m - Ms);
+#pragma unroll
+            for (int k = 0; k < NLD; ++k)
+              if (p0 + NQ * k < nparts)
+                z += __uint_as_float((uint32_t)(bits[k] >> 32)) * fast_exp2(__uint_as_float((uint32_t)bits[k]) - Ms);
+            m = M;
           }
         }
-        red[q][rl] = make_float2(m, z);
+        red[q * kRowBlock + rl] = make_float2(m, z);
         __syncthreads();
         if (q == 0) {
 #pragma unroll
-          for (int k = 1; k < NQ; ++k) merge_stats(m, z, red[k][rl].x, red[k][rl].y);
+          for (int k = 1; k < NQ; ++k) merge_stats(m, z, red[k * kRowBlock + rl].x, red[k * kRowBlock + rl].y);
           // kept as -c_r/kappa (see sweep 2); padding rows get -inf and contribute exp2(-inf) = 0
           const float c = (r < a.R) ? -(m + fast_log2(z)) * a.inv_kappa : -INFINITY;
-          cst[r] = c;
+          cfr[r] = split3(c);
           if (r < a.R) st64(&cbuf[r], ((u64)tag << 32) | __float_as_uint(c));
         }
         __syncthreads();
       }
+#ifdef PKV_RES_TIMING
+      tstamp[3] += wall_clock64();
+#endif
+      if (has_next) {  // before this unit's sweep 2 requests the next keys: loads return in order
+        stage_q(nxt_u, 0, qsmem + (buf ^ 1) * QBUF);
+        q_staged = true;
+      }
     } else {
+      // while the others arrive: the next unit's first block of Q goes into the other LDS buffer
+      if (has_next) {
+        stage_q(nxt_u, 0, qsmem + (buf ^ 1) * QBUF);
+        q_staged = true;
+      }
       for (int r = tid; r < a.Rpad; r += kThreads) {
         float c = -INFINITY;
         if (r < a.R) {
@@ -434,94 +562,128 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
           }
           c = __uint_as_float((unsigned)w);
         }
-        cst[r] = c;
+        cfr[r] = split3(c);
       }
       __syncthreads();
     }
     PKV_T(2);
     PKV_TN(4);
 
-    // ---- 4. sweep 2: normalised probabilities summed over the query rows ----
+    // ---- sweep 2: normalised probabilities summed over the query rows ----
     // Here the product's rows are query rows (element v of a lane: row mrow0(v) + 4*hf of the tile) and its
-    // columns keys (lane & 31).  cst[] holds -c_r/kappa and is the initial accumulator of each product, so the
+    // columns keys (lane & 31).  -c_r/kappa enters each product through one extra MFMA (see below), so the
     // product comes out as (q.k - c_r/kappa) and one multiply + exp2 + add per logit remain.
+    // Again two passes (key tiles 0,1, then 2,3): after a pass its keys are no longer needed, their scores are
+    // written, and the next unit's keys are requested into the same registers.
+    // Every load issued so far has long returned (sweep 1 consumed the keys).  Saying so here keeps the
+    // compiler from waiting, in the second pass, for the next unit's keys requested after the first pass.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    float* raw = a.raw + (size_t)u * a.N;
     float e[kTiles];
 #pragma unroll
     for (int t = 0; t < kTiles; ++t) e[t] = 0.f;
-    for (int rb = 0; rb < a.nrb; ++rb) {
+    // LAST: the final row block; only there are scores written and the next keys requested (kept out of the
+    // row-block loop so that no load appears to be pending on the keys when the loop comes round).
+    auto s2_block = [&](int rb, auto LAST) {
+      constexpr bool last_rb = decltype(LAST)::value;
       if (a.nrb > 1) {
-        u32x4 qv[QLD];
         __syncthreads();
-        stage_q_issue(rb, qv);
-        stage_q_commit(qv);
+        stage_q(cur_u, rb, qb);
         __syncthreads();
       }
       const int rows_here = min(kRowBlock, a.R - rb * kRowBlock);
       const int nrt = (rows_here + 31) / 32;
-      if (has_keys) {
-        bf16x8 qf[KS];
-        f32x16 cinit, cur, nxt;
-        auto load_cinit = [&](int rt, int j) {
-          const f32x4 c = *reinterpret_cast<const f32x4*>(&cst[rb * kRowBlock + 32 * rt + 8 * j + 4 * hf]);
-          cinit[4 * j + 0] = c[0]; cinit[4 * j + 1] = c[1]; cinit[4 * j + 2] = c[2]; cinit[4 * j + 3] = c[3];
-        };
+      bf16x8 qf[KS];
+      f32x16 cur, nxt;
+      // The normalisers enter through one extra MFMA per product: operand A = (hi, mid, lo, 0...) of the
+      // lane's query row in the first wave half (zeros in the second), operand B = (1, 1, 1, 0...).
+      const u32x4 ones_u = (hf == 0) ? u32x4{0x3F803F80u, 0x00003F80u, 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
+      const bf16x8 ones = as_frag(ones_u);
+      const u64* cfr_lane = (hf == 0) ? cfr + rb * kRowBlock + l32 : reinterpret_cast<const u64*>(qsmem + SEG);  // second half: a zero word
+      const int cfr_step = (hf == 0) ? 32 : 0;
+      bf16x8 bfr;
+      auto load_bias = [&](int rt) {
+        const u64 w = cfr_lane[cfr_step * rt];
+        bfr = as_frag(u32x4{(uint32_t)w, (uint32_t)(w >> 32), 0u, 0u});
+      };
+      auto step = [&](auto TC, auto TN, auto RELOAD, auto RFT, auto HALF, const Unit& ru, int rt_next) {
+        constexpr int tc = decltype(TC)::value, tn = decltype(TN)::value;
+        float s0 = 0.f, s1 = 0.f;
+        nxt = PKV_MFMA32(bfr, ones, zero16);
+        if (decltype(RELOAD)::value) load_bias(rt_next);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = q_frag(0, ks);
+        for (int ks = 0; ks < KS; ++ks) {
+          nxt = PKV_MFMA32(qf[ks], kf[tn][ks], nxt);
+          if (decltype(RELOAD)::value) qf[ks] = q_frag(rt_next, ks);  // this row tile's fragments are free: fetch the next tile's
+          float x[TPM], ee[TPM];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) load_cinit(0, j);
-        cur = cinit;
+          for (int j = 0; j < TPM; ++j) x[j] = cur[TPM * ks + j] * a.kappa;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) cur = PKV_MFMA32(qf[ks], kf[0][ks], cur);
-#pragma unroll 1
-        for (int rt = 0; rt < nrt; ++rt) {
-          const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;
+          for (int j = 0; j < TPM; ++j) ee[j] = fast_exp2(x[j]);
 #pragma unroll
-          for (int t = 0; t < kTiles; ++t) {
-            const int tn = (t + 1) % kTiles;
-            float s0 = 0.f, s1 = 0.f;
-            nxt = cinit;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-              nxt = PKV_MFMA32(qf[ks], kf[tn][ks], nxt);
-              if (t == kTiles - 2) {  // this row tile's fragments and normalisers are free: fetch the next tile's
-                qf[ks] = q_frag(rt_next, ks);
-                if (ks < 4) load_cinit(rt_next, ks);
-              }
-              float x[TPM], ee[TPM];
-#pragma unroll
-              for (int j = 0; j < TPM; ++j) x[j] = cur[TPM * ks + j] * a.kappa;
-#pragma unroll
-              for (int j = 0; j < TPM; ++j) ee[j] = fast_exp2(x[j]);
-#pragma unroll
-              for (int j = 0; j < TPM; ++j) {
-                if (j & 1) s1 += ee[j]; else s0 += ee[j];
-              }
-              PKV_SG_MFMA(1);
-              if (t == kTiles - 2) {
-                if (ks < 4) PKV_SG_DSR(2); else PKV_SG_DSR(1);
-              }
-              PKV_SG_VALU(TPM);
-              PKV_SG_TRANS(TPM);
-              PKV_SG_VALU(TPM);
-            }
-            e[t] += s0 + s1;
-            cur = nxt;
+          for (int j = 0; j < TPM; ++j) {
+            if (j & 1) s1 += ee[j]; else s0 += ee[j];
           }
+          PKV_CHUNK_END_SUMS(s0, s1);
+          if (ks == KS / 2 - 1) refill(ru, RFT, HALF);
         }
-      }
-    }
-    if (has_keys) {
-      float* raw = a.raw + (size_t)u * a.N;
+        e[tc] += s0 + s1;
+        cur = nxt;
+      };
+      auto iter = [&](auto TA, auto TB, auto RFT, const Unit& ru, int rt) {
+        const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;
+        step(TA, TB, std::true_type{}, RFT, I0{}, ru, rt_next);
+        step(TB, TA, std::false_type{}, RFT, I1{}, ru, rt_next);
+      };
+      auto pass = [&](auto TA, auto TB, auto REFILL, auto F0, auto F1, const Unit& ru) {
+        constexpr int ta = decltype(TA)::value, tb = decltype(TB)::value;
+        if (has_keys) {
 #pragma unroll
-      for (int t = 0; t < kTiles; ++t) {
-        float tot = e[t];
-        tot += __shfl_xor(tot, 32);
-        const int key = wkey0 + 32 * t + l32;
-        if (hf == 0 && key < npre) raw[key] = tot * a.inv_G;
+          for (int ks = 0; ks < KS; ++ks) qf[ks] = q_frag(0, ks);
+          load_bias(0);
+          cur = PKV_MFMA32(bfr, ones, zero16);
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) cur = PKV_MFMA32(qf[ks], kf[ta][ks], cur);
+          int rt = 0;
+          if constexpr (decltype(REFILL)::value) {
+            iter(TA, TB, F0, ru, 0);
+            if (nrt > 1) iter(TA, TB, F1, ru, 1);
+            else issue_k(ru, F1, I0{}, IKS{});
+            rt = 2;
+          }
+#pragma unroll 1
+          for (; rt < nrt; ++rt) iter(TA, TB, INONE{}, ru, rt);
+          if (last_rb) {
+#pragma unroll
+            for (int t = ta; t <= tb; ++t) {
+              float tot = e[t];
+              tot += __shfl_xor(tot, 32);
+              const int key = wkey0 + 32 * t + l32;
+              if (hf == 0 && key < npre) raw[key] = tot * a.inv_G;
+            }
+          }
+        } else if constexpr (decltype(REFILL)::value) {  // a wave without keys in this unit still fetches the next unit's
+          issue_k(ru, F0, I0{}, IKS{});
+          issue_k(ru, F1, I0{}, IKS{});
+        }
+      };
+      pass(I0{}, I1{}, std::false_type{}, I2{}, I3{}, cur_u);
+      // key tiles 0,1 are done: the next unit's are requested into the same registers during the second pass
+      // (after the last unit the current ones are fetched once more: harmless, and the code stays branch-free)
+      pass(I2{}, I3{}, LAST, I0{}, I1{}, has_next ? nxt_u : cur_u);
+      // ... and key tiles 2,3 right after it: they are needed last, half a sweep from now
+      if constexpr (last_rb) {
+        issue_k(has_next ? nxt_u : cur_u, I2{}, I0{}, IKS{});
+        issue_k(has_next ? nxt_u : cur_u, I3{}, I0{}, IKS{});
       }
-    }
-    __syncthreads();  // cst / qs / red are reused by the next unit
+    };
+    for (int rb = 0; rb + 1 < a.nrb; ++rb) s2_block(rb, std::false_type{});
+    s2_block(a.nrb - 1, std::true_type{});
+    if (has_next && !q_staged) stage_q(nxt_u, 0, qsmem + (buf ^ 1) * QBUF);
+    __syncthreads();  // cfr / stat and the Q buffers change hands
     PKV_T(4);
+    cur_u = nxt_u;
+    buf ^= 1;
   }
 #ifdef PKV_RES_TIMING
   tstamp[5] += clock64();
@@ -538,19 +700,30 @@ __global__ void zero_kernel(int32_t* p, int n) {
 
 }  // namespace
 
+template <int D>
+static hipError_t launch_resident(const ResidentArgs& a, hipStream_t s) {
+  constexpr int SEG = D / 8;
+  const size_t dyn = (size_t)2 * kRowBlock * lds_pitch<SEG>() * sizeof(u32x4);  // two Q buffers
+  static bool attr_set = false;
+  if (!attr_set) {  // raise the dynamic LDS limit once (idempotent; no allocation)
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_resident_kernel<D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(score_resident_kernel<D>, dim3(kResidentGrid), dim3(kThreads), dyn, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s) {
   // the counters, the error word and the tagged normaliser words must start at zero
   const int nz = a.sync_words;
   hipLaunchKernelGGL(zero_kernel, dim3((nz + 255) / 256), dim3(256), 0, s, a.cnt, nz);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (a.d == 128)
-    hipLaunchKernelGGL(score_resident_kernel<128>, dim3(kResidentGrid), dim3(kThreads), 0, s, a);
-  else if (a.d == 64)
-    hipLaunchKernelGGL(score_resident_kernel<64>, dim3(kResidentGrid), dim3(kThreads), 0, s, a);
-  else
-    return hipErrorInvalidValue;
-  return hipGetLastError();
+  if (a.d == 128) return launch_resident<128>(a, s);
+  if (a.d == 64) return launch_resident<64>(a, s);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace pkv

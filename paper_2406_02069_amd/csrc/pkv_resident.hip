@@ -364,15 +364,16 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         // One step of the pipeline: issue the MFMAs of the product (TN, current qf) and meanwhile turn the
         // finished product `cur` of tile TC into exponentials.  RELOAD: the issued product is the last use
         // of qf, which is refilled for row tile rt_next as the MFMAs go out.
-        auto step = [&](auto TC, auto TN, auto FIRST, auto RELOAD, auto RFT, auto HALF, const Unit& ru, int rt,
+        auto step = [&](auto TC, auto TN, auto FIRST, auto RELOAD, auto ISSUE, auto RFT, auto HALF, const Unit& ru, int rt,
                         int rt_next, float& m, float& z) {
           constexpr int tc = decltype(TC)::value, tn = decltype(TN)::value;
+          constexpr bool issue = decltype(ISSUE)::value;  // false: the pass ends here, no further product
           if (dirty_mask & (1 << tc)) {
             // slow variant (masks, exact update); the next product is still issued first
             nxt = zero16;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-              nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
+              if (issue) nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
               if (decltype(RELOAD)::value) qf[ks] = q_frag(rt_next, ks);
             }
             refill(ru, RFT, HALF);
@@ -387,7 +388,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
             nxt = zero16;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-              nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
+              if (issue) nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
               if (decltype(RELOAD)::value) qf[ks] = q_frag(rt_next, ks);  // last use of this fragment was the MFMA above
               float x[TPM], e[TPM];
 #pragma unroll
@@ -409,15 +410,16 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         using T = std::true_type;
         // both products of one row tile with the key tiles (TA, TB); RFT: key tile refilled meanwhile
         auto iter = [&](auto TA, auto TB, auto FIRSTPASS, auto RFT, const Unit& ru, int rt) {
-          const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;  // after the last tile one unused product is issued
+          const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;  // (the last reload of the pass is not used)
           float m = -INFINITY, z = 0.f;  // m: reference exponent of this lane (not necessarily the maximum)
           if (!decltype(FIRSTPASS)::value) {
             const float2 st = stat[wave][hf][32 * rt + l32];
             m = st.x;
             z = st.y;
           }
-          step(TA, TB, FIRSTPASS, T{}, RFT, I0{}, ru, rt, rt_next, m, z);
-          step(TB, TA, F{}, F{}, RFT, I1{}, ru, rt, rt_next, m, z);
+          step(TA, TB, FIRSTPASS, T{}, T{}, RFT, I0{}, ru, rt, rt_next, m, z);
+          if (rt + 1 < nrt) step(TB, TA, F{}, F{}, T{}, RFT, I1{}, ru, rt, rt_next, m, z);
+          else step(TB, TA, F{}, F{}, F{}, RFT, I1{}, ru, rt, rt_next, m, z);  // last product of the pass
           stat[wave][hf][32 * rt + l32] = make_float2(m, z);
           // a sum outside the safe range (or NaN) means the provisional reference was too far off
           if (!decltype(FIRSTPASS)::value && __any(!(z <= 0x1p100f))) redo |= 1 << rt;
@@ -606,14 +608,15 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         const u64 w = cfr_lane[cfr_step * rt];
         bfr = as_frag(u32x4{(uint32_t)w, (uint32_t)(w >> 32), 0u, 0u});
       };
-      auto step = [&](auto TC, auto TN, auto RELOAD, auto RFT, auto HALF, const Unit& ru, int rt_next) {
+      auto step = [&](auto TC, auto TN, auto RELOAD, auto ISSUE, auto RFT, auto HALF, const Unit& ru, int rt_next) {
         constexpr int tc = decltype(TC)::value, tn = decltype(TN)::value;
+        constexpr bool issue = decltype(ISSUE)::value;  // false: the pass ends here, no further product
         float s0 = 0.f, s1 = 0.f;
-        nxt = PKV_MFMA32(bfr, ones, zero16);
+        if (issue) nxt = PKV_MFMA32(bfr, ones, zero16);
         if (decltype(RELOAD)::value) load_bias(rt_next);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          nxt = PKV_MFMA32(qf[ks], kf[tn][ks], nxt);
+          if (issue) nxt = PKV_MFMA32(qf[ks], kf[tn][ks], nxt);
           if (decltype(RELOAD)::value) qf[ks] = q_frag(rt_next, ks);  // this row tile's fragments are free: fetch the next tile's
           float x[TPM], ee[TPM];
 #pragma unroll
@@ -632,8 +635,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       };
       auto iter = [&](auto TA, auto TB, auto RFT, const Unit& ru, int rt) {
         const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;
-        step(TA, TB, std::true_type{}, RFT, I0{}, ru, rt_next);
-        step(TB, TA, std::false_type{}, RFT, I1{}, ru, rt_next);
+        step(TA, TB, std::true_type{}, std::true_type{}, RFT, I0{}, ru, rt_next);
+        if (rt + 1 < nrt) step(TB, TA, std::false_type{}, std::true_type{}, RFT, I1{}, ru, rt_next);
+        else step(TB, TA, std::false_type{}, std::false_type{}, RFT, I1{}, ru, rt_next);  // last product of the pass
       };
       auto pass = [&](auto TA, auto TB, auto REFILL, auto F0, auto F1, const Unit& ru) {
         constexpr int ta = decltype(TA)::value, tb = decltype(TB)::value;

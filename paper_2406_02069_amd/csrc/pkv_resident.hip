@@ -265,7 +265,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       kf[t][ks] = as_frag(*reinterpret_cast<const u32x4*>(rowp + 32 * ks));
   };
   using IKS = std::integral_constant<int, KS>;
-  using IKH = std::integral_constant<int, KS / 2>;
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
   using I2 = std::integral_constant<int, 2>;

@@ -3,13 +3,14 @@
 //
 // One 1024-thread workgroup per unit (layer x sequence x KV head); all layers of a call run in one
 // launch.
-//   A. pooled[i] = pool_w-wide max / average of the un-pooled scores, prefix only, staged tile by tile
-//      through LDS; the fp32 bit patterns become the selection keys (scores are >= 0, so unsigned
-//      order = numeric order).  Keys stay in LDS when the prefix fits (<= 32768 keys), otherwise they
-//      are re-read from the pooled array in global memory.
-//   B. radix select: three digit levels (11 + 11 + 10 bits); each level builds an LDS histogram of the
-//      keys that match the digits found so far and a suffix scan locates the digit holding the kk-th
-//      largest key.  The result is the exact threshold T and how many keys equal to T are needed.
+//   A. pooled[i] = pool_w-wide max / average of the un-pooled scores, prefix only.  When the prefix fits in
+//      LDS (<= 32768 keys) all loads are issued at once, the scores are pooled out of LDS into registers
+//      (32 positions per thread) and written back as keys; longer prefixes go tile by tile through LDS and
+//      keep their keys in the pooled array in global memory.  The fp32 bit patterns are the selection keys
+//      (scores are >= 0, so unsigned order = numeric order).
+//   B. the kk-th largest key T and how many keys equal to T are needed.  Keys in registers: bit by bit from
+//      the top, each bit decided by a ballot/pop-count census of the workgroup (31 barriers, no atomics).
+//      Keys in global memory: radix select, three digit levels (11 + 11 + 10 bits) with LDS histograms.
 //   C. ordered emission: every wave owns a contiguous range of positions; ballots give each kept key
 //      its rank, so positions with key > T, and the lowest positions with key == T, come out in
 //      ascending order, followed by the window positions.
@@ -58,46 +59,117 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
   auto key_at = [&](int i) -> uint32_t { return LDSKEYS ? lkeys[i] : gkeys[i]; };
 
   // ---- A. group mean + pooling ----
+  constexpr int PER = kLdsKeys / NT;   // positions per thread when the prefix lives in LDS
+  uint32_t rkeys[PER];                 // their pooled keys (0: no such position)
   const int r = (pool == PKV_POOL_NONE) ? 0 : (pool_w - 1) / 2;
   const bool is_max = pool == PKV_POOL_MAX;
   const float inv_w = 1.0f / (float)pool_w;
-  for (int t0 = 0; t0 < npre; t0 += TS) {
-    for (int e = tid; e < TS + 2 * r; e += NT) {
-      const int i = t0 - r + e;
-      float v = is_max ? -INFINITY : 0.f;
-      if (i >= 0 && i < npre) {
-        float s = 0.f;
-        for (int q = 0; q < nrb; ++q) s += raw[q * rb_stride + i];
-        v = s * inv_G;
-      }
-      tilebuf[e] = v;
+  if (LDSKEYS) {
+    // The whole prefix fits in LDS: every load of the un-pooled scores is in flight at once (one memory round
+    // trip), then each thread pools its positions from LDS into registers and the pooled keys replace them.
+    float* lsc = reinterpret_cast<float*>(lkeys);
+    float v[PER];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int i = tid + NT * j;
+      float sacc = 0.f;
+      if (i < npre)
+        for (int q = 0; q < nrb; ++q) sacc += raw[q * rb_stride + i];
+      v[j] = sacc * inv_G;
+    }
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int i = tid + NT * j;
+      if (i < npre) lsc[i] = v[j];
     }
     __syncthreads();
-    for (int e = tid; e < TS; e += NT) {
-      const int i = t0 + e;
-      if (i < npre) {
-        float v;
-        if (r == 0) {
-          v = tilebuf[e];
-        } else if (is_max) {
-          v = tilebuf[e];
-          for (int u = 1; u <= 2 * r; ++u) v = fmaxf(v, tilebuf[e + u]);
-        } else {
-          v = 0.f;
-          for (int u = 0; u <= 2 * r; ++u) v += tilebuf[e + u];
-          v *= inv_w;
+    if (r > 0) {
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        const int i = tid + NT * j;
+        if (i < npre) {
+          const int lo = max(i - r, 0), hi = min(i + r, npre - 1);
+          float acc = is_max ? -INFINITY : 0.f;
+          for (int u = lo; u <= hi; ++u) acc = is_max ? fmaxf(acc, lsc[u]) : acc + lsc[u];
+          v[j] = is_max ? acc : acc * inv_w;
         }
-        if (LDSKEYS) lkeys[i] = __float_as_uint(v);
-        if (!LDSKEYS || write_pooled) pooled[i] = v;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        const int i = tid + NT * j;
+        if (i < npre) lsc[i] = v[j];
       }
     }
+    if (write_pooled) {
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        const int i = tid + NT * j;
+        if (i < npre) pooled[i] = v[j];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < PER; ++j) rkeys[j] = (tid + NT * j < npre) ? __float_as_uint(v[j]) : 0u;
     __syncthreads();
+  } else {
+    for (int t0 = 0; t0 < npre; t0 += TS) {
+      for (int e = tid; e < TS + 2 * r; e += NT) {
+        const int i = t0 - r + e;
+        float v = is_max ? -INFINITY : 0.f;
+        if (i >= 0 && i < npre) {
+          float s = 0.f;
+          for (int q = 0; q < nrb; ++q) s += raw[q * rb_stride + i];
+          v = s * inv_G;
+        }
+        tilebuf[e] = v;
+      }
+      __syncthreads();
+      for (int e = tid; e < TS; e += NT) {
+        const int i = t0 + e;
+        if (i < npre) {
+          float v;
+          if (r == 0) {
+            v = tilebuf[e];
+          } else if (is_max) {
+            v = tilebuf[e];
+            for (int u = 1; u <= 2 * r; ++u) v = fmaxf(v, tilebuf[e + u]);
+          } else {
+            v = 0.f;
+            for (int u = 0; u <= 2 * r; ++u) v += tilebuf[e + u];
+            v *= inv_w;
+          }
+          pooled[i] = v;
+        }
+      }
+      __syncthreads();
+    }
   }
 
   if (kk > 0) {
-    // ---- B. radix select of the kk-th largest key ----
-    uint32_t prefix = 0, prefix_mask = 0;
+    // ---- B. the kk-th largest key ----
+    uint32_t prefix = 0;
     uint32_t remaining = (uint32_t)kk;
+    if (LDSKEYS) {
+      // Keys sit in registers: the threshold is found bit by bit from the top (scores are >= 0, bit 31 is
+      // clear).  Per bit: count the keys that agree with the bits fixed so far and have this bit set; if
+      // there are at least `remaining` of them the bit is set, else they all rank above the threshold.
+      // Counting is ballots + scalar pop-counts: no LDS atomics, nothing that depends on timing.
+      for (int bit = 30; bit >= 0; --bit) {
+        const uint32_t cand = (prefix >> bit) | 1u;
+        uint32_t wcount = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) wcount += __popcll(__ballot((rkeys[j] >> bit) == cand));
+        uint32_t* slot = scan32 + ((bit & 1) ? NW : 0);  // two sets of per-wave slots: one barrier per bit
+        if (lane == 0) slot[wave] = wcount;
+        __syncthreads();
+        uint32_t c = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) c += slot[w];
+        if (c >= remaining) prefix |= 1u << bit;
+        else remaining -= c;
+      }
+    } else {
+    uint32_t prefix_mask = 0;
     const int shifts[3] = {21, 10, 0};
     const int bits[3] = {11, 11, 10};
 #pragma unroll
@@ -130,6 +202,7 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       prefix_mask |= dmask << shift;
       remaining -= sel[1];
       __syncthreads();
+    }
     }
     const uint32_t T = prefix;           // bit pattern of the kk-th largest pooled score
     const uint32_t need_eq = remaining;  // keys equal to T to take, lowest positions first (>= 1)
@@ -176,7 +249,7 @@ __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatch
   extern __shared__ uint32_t lkeys[];  // kLdsKeys entries
   __shared__ float tilebuf[TS + 2 * 32];
   __shared__ uint32_t hist[HIST];
-  __shared__ uint32_t scan32[NW];
+  __shared__ uint32_t scan32[2 * NW];
   __shared__ uint32_t sel[2];
 
   const int tid = threadIdx.x;

@@ -261,7 +261,7 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
     se.pool_w = d.pool_w;
     se.nrb = nrb;
     se.inv_G = resident ? 1.0f : 1.0f / (float)plan.G;
-    ga.L = nl; ga.B = d.B; ga.Hkv = d.Hkv; ga.d = d.d; ga.k_cap_max = k_cap_max;
+    ga.L = nl; ga.B = d.B; ga.Hkv = d.Hkv; ga.d = d.d; ga.k_cap_max = k_cap_max; ga.N = d.N;
     ga.kv_sb = d.kv_sb; ga.kv_sh = d.kv_sh; ga.kv_st = d.kv_st;
     if (launch_pool_select_batch(se, nl, stream) != hipSuccess) return PKV_ERR_HIP;
     if (rec) rec->after(PKV_KERNEL_POOL_SELECT, stream);

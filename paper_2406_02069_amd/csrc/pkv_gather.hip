@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void gather_batch_kernel(const GatherBatchArgs
   if (j >= ly.k_cap) return;
   const int src = ly.idx[(size_t)bg * ly.k_cap + j];
   uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
-  if (src >= 0) {
+  if ((uint32_t)src < (uint32_t)a.N) {  // -1 marks an unused slot; anything else out of range is not dereferenced either
     const size_t off = (size_t)b * a.kv_sb + (size_t)g * a.kv_sh + (size_t)src * a.kv_st + seg * 8;
     kv = *reinterpret_cast<const uint4*>(ly.K + off);
     vv = *reinterpret_cast<const uint4*>(ly.V + off);

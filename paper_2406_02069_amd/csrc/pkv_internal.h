@@ -124,6 +124,7 @@ struct GatherLayer {
 struct GatherBatchArgs {
   GatherLayer layer[kBatchMaxLayers];
   int32_t L, B, Hkv, d, k_cap_max;
+  int32_t N;  // rows per head in K and V: positions outside [0, N) are never dereferenced
   int64_t kv_sb, kv_sh, kv_st;
 };
 

@@ -9,7 +9,7 @@
 //      keep their keys in the pooled array in global memory.  The fp32 bit patterns are the selection keys
 //      (scores are >= 0, so unsigned order = numeric order).
 //   B. the kk-th largest key T and how many keys equal to T are needed.  Keys in registers: bit by bit from
-//      the top, each bit decided by a ballot/pop-count census of the workgroup (31 barriers, no atomics).
+//      the top, each bit decided by a ballot/pop-count census of the workgroup (32 barriers, no atomics).
 //      Keys in global memory: radix select, three digit levels (11 + 11 + 10 bits) with LDS histograms.
 //   C. ordered emission: every wave owns a contiguous range of positions; ballots give each kept key
 //      its rank, so positions with key > T, and the lowest positions with key == T, come out in
@@ -150,11 +150,12 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
     uint32_t prefix = 0;
     uint32_t remaining = (uint32_t)kk;
     if (LDSKEYS) {
-      // Keys sit in registers: the threshold is found bit by bit from the top (scores are >= 0, bit 31 is
-      // clear).  Per bit: count the keys that agree with the bits fixed so far and have this bit set; if
-      // there are at least `remaining` of them the bit is set, else they all rank above the threshold.
+      // Keys sit in registers: the threshold is found bit by bit from the top.  Per bit: count the keys that
+      // agree with the bits fixed so far and have this bit set; if there are at least `remaining` of them the
+      // bit is set, else they all rank above the threshold.  All 32 bits are searched although scores are
+      // >= 0: whatever bit patterns the scores hold (NaN, negative zero), exactly kk positions are selected.
       // Counting is ballots + scalar pop-counts: no LDS atomics, nothing that depends on timing.
-      for (int bit = 30; bit >= 0; --bit) {
+      for (int bit = 31; bit >= 0; --bit) {
         const uint32_t cand = (prefix >> bit) | 1u;
         uint32_t wcount = 0;
 #pragma unroll

@@ -63,7 +63,7 @@ Plan make_plan(const pkv_layer_desc& d, int L) {
   p.off_pooled = off;
   off += align256(U * d.N * sizeof(float));
   p.off_dbg = off;
-  off += align256(((size_t)kResidentGrid * 8 + 1024) * sizeof(long long));
+  off += align256(((size_t)kResidentGrid * 16 + 1024) * sizeof(long long));
   p.total = off;
   return p;
 }

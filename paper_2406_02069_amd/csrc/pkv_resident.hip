@@ -607,19 +607,26 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         const u64 w = cfr_lane[cfr_step * rt];
         bfr = as_frag(u32x4{(uint32_t)w, (uint32_t)(w >> 32), 0u, 0u});
       };
-      auto step = [&](auto TC, auto TN, auto RELOAD, auto ISSUE, auto RFT, auto HALF, const Unit& ru, int rt_next) {
+      // `fin` holds the finished product of tile TC; the product of tile TN goes into `out` (the two accumulators
+      // swap roles from step to step, so nothing is ever copied)
+      auto step = [&](auto TC, auto TN, auto RELOAD, auto ISSUE, auto RFT, auto HALF, const Unit& ru, int rt_next,
+                      const f32x16& fin, f32x16& out) {
         constexpr int tc = decltype(TC)::value, tn = decltype(TN)::value;
         constexpr bool issue = decltype(ISSUE)::value;  // false: the pass ends here, no further product
         float s0 = 0.f, s1 = 0.f;
-        if (issue) nxt = PKV_MFMA32(bfr, ones, zero16);
+        // a scale factor of its own for every instance of this step: identical multiplies in the two arms of a
+        // branch would otherwise be merged in front of it, away from the MFMAs they are meant to run under
+        float kap = a.kappa;
+        asm volatile("" : "+s"(kap));
+        if (issue) out = PKV_MFMA32(bfr, ones, zero16);
         if (decltype(RELOAD)::value) load_bias(rt_next);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          if (issue) nxt = PKV_MFMA32(qf[ks], kf[tn][ks], nxt);
+          if (issue) out = PKV_MFMA32(qf[ks], kf[tn][ks], out);
           if (decltype(RELOAD)::value) qf[ks] = q_frag(rt_next, ks);  // this row tile's fragments are free: fetch the next tile's
           float x[TPM], ee[TPM];
 #pragma unroll
-          for (int j = 0; j < TPM; ++j) x[j] = cur[TPM * ks + j] * a.kappa;
+          for (int j = 0; j < TPM; ++j) x[j] = fin[TPM * ks + j] * kap;
 #pragma unroll
           for (int j = 0; j < TPM; ++j) ee[j] = fast_exp2(x[j]);
 #pragma unroll
@@ -630,13 +637,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
           if (ks == KS / 2 - 1) refill(ru, RFT, HALF);
         }
         e[tc] += s0 + s1;
-        cur = nxt;
       };
       auto iter = [&](auto TA, auto TB, auto RFT, const Unit& ru, int rt) {
         const int rt_next = (rt + 1 < nrt) ? rt + 1 : 0;
-        step(TA, TB, std::true_type{}, std::true_type{}, RFT, I0{}, ru, rt_next);
-        if (rt + 1 < nrt) step(TB, TA, std::false_type{}, std::true_type{}, RFT, I1{}, ru, rt_next);
-        else step(TB, TA, std::false_type{}, std::false_type{}, RFT, I1{}, ru, rt_next);  // last product of the pass
+        step(TA, TB, std::true_type{}, std::true_type{}, RFT, I0{}, ru, rt_next, cur, nxt);
+        if (rt + 1 < nrt) step(TB, TA, std::false_type{}, std::true_type{}, RFT, I1{}, ru, rt_next, nxt, cur);
+        else step(TB, TA, std::false_type{}, std::false_type{}, RFT, I1{}, ru, rt_next, nxt, cur);  // last product of the pass
       };
       auto pass = [&](auto TA, auto TB, auto REFILL, auto F0, auto F1, const Unit& ru) {
         constexpr int ta = decltype(TA)::value, tb = decltype(TB)::value;

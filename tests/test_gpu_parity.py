@@ -160,3 +160,52 @@ def test_compress_layers_equals_per_layer_calls_and_budget_nesting():
         if prev is not None:
             assert all(p <= c for p, c in zip(prev, cur))
         prev = cur
+
+
+def test_extreme_logits_take_the_exact_fallback(score_path):
+    # Keys aligned with a window query and scaled x8 give logits near 8*|q|^2 ~ 1000: about 130 binary orders
+    # above their neighbours' after the 1/sqrt(d) scaling, beyond what a fixed reference exponent can
+    # carry in fp32.  Planted away from the first keys of a 128-key span, in the middle of the prefix and
+    # inside the last, masked tile; also a strongly negative one (-8x).
+    alpha, N, B, Hq, Hkv, d = 32, 2000, 2, 8, 2, 128
+    Q, K, V = _rand(B, Hq, Hkv, d, N, alpha, seed=11)
+    K[0, 0, 77] = (Q[0, 1, 3].float() * 8).to(torch.bfloat16)          # head group 0: query heads 0..3
+    K[0, 0, 700] = (Q[0, 2, 31].float() * 8).to(torch.bfloat16)
+    K[0, 1, 1] = (Q[0, 5, 0].float() * 8).to(torch.bfloat16)           # head group 1: query heads 4..7
+    K[0, 1, N - alpha - 2] = (Q[0, 7, 30].float() * 8).to(torch.bfloat16)
+    K[1, 0, 1300] = (Q[1, 0, 16].float() * -8).to(torch.bfloat16)
+    K[1, 1, 515] = (Q[1, 6, 9].float() * 8).to(torch.bfloat16)
+    for pool, pw in ((synth.POOL_AVG, 5), (synth.POOL_NONE, 1)):
+        print("extreme logits", pool, pw, flush=True)
+        st, out = _run_and_compare(_W(alpha, pool, pw), 0, alpha + 96, Q, K, V)
+        kept = out[2].cpu().numpy()
+        assert 77 in kept[0, 0] and 700 in kept[0, 0] and 1 in kept[0, 1] and 515 in kept[1, 1]
+
+
+def test_non_finite_inputs_stay_in_bounds(score_path):
+    # NaN / Inf in one head's keys make that head's scores NaN.  Whatever is kept there must still be a valid
+    # selection (in range, ascending, window present, rows copied bit for bit); every other unit is unaffected.
+    alpha, N, B, Hq, Hkv, d, k_l = 8, 1500, 2, 8, 2, 128, 72
+    Q, K, V = _rand(B, Hq, Hkv, d, N, alpha, seed=12)
+    w = _W(alpha, synth.POOL_MAX, 7)
+    clean = binding.compress_layer(Q, K, V, k_l, w.pool, w.pool_w, want_scores=True)
+    torch.cuda.synchronize()
+    Kbad = K.clone()
+    Kbad[0, 0, 100] = float("nan")
+    Kbad[0, 0, 900, 5] = float("inf")
+    Kbad[0, 0, 901, 6] = float("-inf")
+    out = binding.compress_layer(Q, Kbad, V, k_l, w.pool, w.pool_w, want_scores=True)
+    torch.cuda.synchronize()
+    idx = out[2].cpu().numpy()
+    assert out[3].cpu().tolist() == [k_l, k_l]
+    for b in range(B):
+        for g in range(Hkv):
+            row = idx[b, g]
+            assert row.min() >= 0 and row.max() < N and np.all(np.diff(row) > 0), (b, g)
+            assert row[-alpha:].tolist() == list(range(N - alpha, N)), (b, g)
+            sel = torch.from_numpy(row.astype(np.int64)).to(DEV)
+            assert np.array_equal(bits(out[0][b, g]), bits(Kbad[b, g].index_select(0, sel)))
+            assert np.array_equal(bits(out[1][b, g]), bits(V[b, g].index_select(0, sel)))
+            if (b, g) != (0, 0):
+                assert np.array_equal(row, clean[2][b, g].cpu().numpy()), (b, g)
+                assert torch.equal(out[4][b, g], clean[4][b, g])

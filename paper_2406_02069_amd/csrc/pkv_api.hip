@@ -63,7 +63,7 @@ Plan make_plan(const pkv_layer_desc& d, int L) {
   p.off_pooled = off;
   off += align256(U * d.N * sizeof(float));
   p.off_dbg = off;
-  off += align256(((size_t)kResidentGrid * 16 + 1024) * sizeof(long long));
+  off += align256(((size_t)kResidentGrid * 16 + 1024 + 256 * 8) * sizeof(long long));
   p.total = off;
   return p;
 }
@@ -261,6 +261,7 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
     se.pool_w = d.pool_w;
     se.nrb = nrb;
     se.inv_G = resident ? 1.0f : 1.0f / (float)plan.G;
+    se.dbg = reinterpret_cast<long long*>(ws + plan.off_dbg) + kResidentGrid * 16 + 1024;
     ga.L = nl; ga.B = d.B; ga.Hkv = d.Hkv; ga.d = d.d; ga.k_cap_max = k_cap_max; ga.N = d.N;
     ga.kv_sb = d.kv_sb; ga.kv_sh = d.kv_sh; ga.kv_st = d.kv_st;
     if (launch_pool_select_batch(se, nl, stream) != hipSuccess) return PKV_ERR_HIP;

@@ -109,6 +109,7 @@ struct SelectBatchArgs {
   int32_t B, Hkv, N, alpha, pool, pool_w;
   int32_t nrb;         // partial score arrays to add per layer
   float inv_G;         // factor applied to the sum of the partials
+  long long* dbg;      // per-unit phase timers (development builds only), may be null
 };
 
 struct GatherLayer {

@@ -5,16 +5,20 @@
 // launch.
 //   A. pooled[i] = pool_w-wide max / average of the un-pooled scores, prefix only.  When the prefix fits in
 //      LDS (<= 32768 keys) all loads are issued at once, the scores are pooled out of LDS into registers
-//      (32 positions per thread) and written back as keys; longer prefixes go tile by tile through LDS and
-//      keep their keys in the pooled array in global memory.  The fp32 bit patterns are the selection keys
-//      (scores are >= 0, so unsigned order = numeric order).
-//   B. the kk-th largest key T and how many keys equal to T are needed.  Keys in registers: bit by bit from
-//      the top, each bit decided by a ballot/pop-count census of the workgroup (32 barriers, no atomics).
+//      (32 positions per thread, each wave owning a contiguous range of 2048 positions) and stay there; longer
+//      prefixes go tile by tile through LDS and keep their keys in the pooled array in global memory.  The
+//      fp32 bit patterns are the selection keys (scores are >= 0, so unsigned order = numeric order).
+//   B. the kk-th largest key T.  Keys in registers: binary search on T, one bit per round from the top; a
+//      round counts the keys >= the candidate (per lane, then per wave through ballots, then 16 wave counts
+//      through LDS: one barrier, no atomics).  As soon as at most 1024 keys still agree with the decided
+//      bits, those keys move to a list and the remaining rounds look at one key per thread.
 //      Keys in global memory: radix select, three digit levels (11 + 11 + 10 bits) with LDS histograms.
 //   C. ordered emission: every wave owns a contiguous range of positions; ballots give each kept key
 //      its rank, so positions with key > T, and the lowest positions with key == T, come out in
 //      ascending order, followed by the window positions.
 // All counters are integers and the emission is ordered, so the result does not depend on scheduling.
+#include <type_traits>
+
 #include "pkv_internal.h"
 
 namespace pkv {
@@ -48,45 +52,106 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* s
   return v + base;
 }
 
+#ifdef PKV_SEL_TIMING
+#define PKV_ST(i) do { if (threadIdx.x == 0 && blockIdx.x < 256 && g_dbg) g_dbg[blockIdx.x * 8 + i] = clock64(); } while (0)
+#else
+#define PKV_ST(i)
+#endif
+
 template <bool LDSKEYS>
 __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb_stride, float inv_G, float* pooled,
                                             bool write_pooled, int32_t* idx, int npre, int kk, int alpha, int pool,
                                             int pool_w, uint32_t* lkeys, float* tilebuf, uint32_t* hist,
-                                            uint32_t* scan32, uint32_t* sel) {
+                                            uint32_t* scan32, uint32_t* sel, long long* g_dbg) {
   const int tid = threadIdx.x;
+  PKV_ST(0);
   const int lane = tid & 63, wave = tid >> 6;
   const uint32_t* gkeys = reinterpret_cast<const uint32_t*>(pooled);
   auto key_at = [&](int i) -> uint32_t { return LDSKEYS ? lkeys[i] : gkeys[i]; };
 
   // ---- A. group mean + pooling ----
   constexpr int PER = kLdsKeys / NT;   // positions per thread when the prefix lives in LDS
-  uint32_t rkeys[PER];                 // their pooled keys (0: no such position)
+  constexpr int CW = kLdsKeys / NW;    // ... and per wave: wave w owns positions [w * CW, (w + 1) * CW)
+  uint32_t rkeys[PER];                 // pooled keys of positions wave * CW + 64 * j + lane (0: no such position)
   const int r = (pool == PKV_POOL_NONE) ? 0 : (pool_w - 1) / 2;
   const bool is_max = pool == PKV_POOL_MAX;
   const float inv_w = 1.0f / (float)pool_w;
+  const int pos0 = wave * CW + lane;   // the thread's first position; the others follow in steps of 64
   if (LDSKEYS) {
     // The whole prefix fits in LDS: every load of the un-pooled scores is in flight at once (one memory round
-    // trip), then each thread pools its positions from LDS into registers and the pooled keys replace them.
+    // trip), then each thread pools its positions out of LDS; the pooled values stay in registers, already in
+    // the order in which positions are emitted later (each wave owns a contiguous range).
     float* lsc = reinterpret_cast<float*>(lkeys);
     float v[PER];
+    if (nrb == 1) {
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
-      const int i = tid + NT * j;
-      float sacc = 0.f;
-      if (i < npre)
-        for (int q = 0; q < nrb; ++q) sacc += raw[q * rb_stride + i];
-      v[j] = sacc * inv_G;
+      for (int j = 0; j < PER; ++j) {
+        const int i = pos0 + 64 * j;
+        v[j] = (i < npre) ? raw[i] : 0.f;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        const int i = pos0 + 64 * j;
+        float sacc = 0.f;
+        if (i < npre)
+          for (int q = 0; q < nrb; ++q) sacc += raw[q * rb_stride + i];
+        v[j] = sacc;
+      }
     }
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-      const int i = tid + NT * j;
+      const int i = pos0 + 64 * j;
+      v[j] *= inv_G;
       if (i < npre) lsc[i] = v[j];
     }
     __syncthreads();
-    if (r > 0) {
+    PKV_ST(1);
+    // window of half-width R around position i, summed (or maximised) in ascending position order.  A group of
+    // 64 positions whose windows lie inside the prefix reads with constant offsets and no predicates.
+    auto pool_fixed = [&](auto RR, auto MX) {
+      constexpr int R = decltype(RR)::value;
+      constexpr bool mx = decltype(MX)::value;
+      const float* lp = lsc + pos0;
 #pragma unroll
       for (int j = 0; j < PER; ++j) {
-        const int i = tid + NT * j;
+        const int g0 = wave * CW + 64 * j;  // first position of the group (wave-uniform)
+        float acc;
+        if (g0 - R >= 0 && g0 + 63 + R < npre) {
+          acc = lp[64 * j - R];
+#pragma unroll
+          for (int u = -R + 1; u <= R; ++u) acc = mx ? fmaxf(acc, lp[64 * j + u]) : acc + lp[64 * j + u];
+          v[j] = mx ? acc : acc * inv_w;
+        } else if (g0 < npre) {
+          const int i = g0 + lane;
+          acc = mx ? -INFINITY : 0.f;
+#pragma unroll
+          for (int u = -R; u <= R; ++u) {
+            const int p = i + u;
+            const bool ok = p >= 0 && p < npre;
+            const float x = lsc[ok ? p : 0];
+            if (mx) acc = ok ? fmaxf(acc, x) : acc;
+            else acc += ok ? x : 0.f;
+          }
+          if (i < npre) v[j] = mx ? acc : acc * inv_w;
+        }
+      }
+    };
+    using std::integral_constant;
+    if (r >= 1 && r <= 3) {
+      if (is_max) {
+        if (r == 1) pool_fixed(integral_constant<int, 1>{}, std::true_type{});
+        else if (r == 2) pool_fixed(integral_constant<int, 2>{}, std::true_type{});
+        else pool_fixed(integral_constant<int, 3>{}, std::true_type{});
+      } else {
+        if (r == 1) pool_fixed(integral_constant<int, 1>{}, std::false_type{});
+        else if (r == 2) pool_fixed(integral_constant<int, 2>{}, std::false_type{});
+        else pool_fixed(integral_constant<int, 3>{}, std::false_type{});
+      }
+    }
+    else if (r > 3) {
+      for (int j = 0; j < PER; ++j) {
+        const int i = pos0 + 64 * j;
         if (i < npre) {
           const int lo = max(i - r, 0), hi = min(i + r, npre - 1);
           float acc = is_max ? -INFINITY : 0.f;
@@ -94,23 +159,17 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
           v[j] = is_max ? acc : acc * inv_w;
         }
       }
-      __syncthreads();
-#pragma unroll
-      for (int j = 0; j < PER; ++j) {
-        const int i = tid + NT * j;
-        if (i < npre) lsc[i] = v[j];
-      }
     }
     if (write_pooled) {
 #pragma unroll
       for (int j = 0; j < PER; ++j) {
-        const int i = tid + NT * j;
+        const int i = pos0 + 64 * j;
         if (i < npre) pooled[i] = v[j];
       }
     }
 #pragma unroll
-    for (int j = 0; j < PER; ++j) rkeys[j] = (tid + NT * j < npre) ? __float_as_uint(v[j]) : 0u;
-    __syncthreads();
+    for (int j = 0; j < PER; ++j) rkeys[j] = (pos0 + 64 * j < npre) ? __float_as_uint(v[j]) : 0u;
+    PKV_ST(2);
   } else {
     for (int t0 = 0; t0 < npre; t0 += TS) {
       for (int e = tid; e < TS + 2 * r; e += NT) {
@@ -150,24 +209,70 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
     uint32_t prefix = 0;
     uint32_t remaining = (uint32_t)kk;
     if (LDSKEYS) {
-      // Keys sit in registers: the threshold is found bit by bit from the top.  Per bit: count the keys that
-      // agree with the bits fixed so far and have this bit set; if there are at least `remaining` of them the
-      // bit is set, else they all rank above the threshold.  All 32 bits are searched although scores are
-      // >= 0: whatever bit patterns the scores hold (NaN, negative zero), exactly kk positions are selected.
-      // Counting is ballots + scalar pop-counts: no LDS atomics, nothing that depends on timing.
+      // Keys sit in registers: binary search for the largest T with count(key >= T) >= kk, one bit per round
+      // from the top.  Per round every lane counts its own keys, the wave adds the lane counts up (ballots over
+      // the bits of the count: no LDS atomics, nothing that depends on timing) and the 16 wave counts meet in LDS:
+      // one barrier per bit.  All 32 bits are searched although scores are >= 0: whatever bit patterns the scores
+      // hold (NaN, negative zero), exactly kk positions are selected.  Positions that do not exist carry key 0
+      // and are never counted (T >= 1 in every comparison).
+      //
+      // Bookkeeping that comes for free: U = number of keys that still agree with the decided bits (the only
+      // ones whose comparison is open), G = number of keys above all of them.  Once U fits one key per thread
+      // the open keys are moved to a list in LDS and the remaining rounds compare one key per thread.
+      uint32_t U = (uint32_t)npre, G = 0;
+      uint32_t G_list = 0;  // keys above every key of the list (fixed once the list exists)
+      bool compacted = false;
+      uint32_t ck = 0;  // the thread's key after compaction
+      uint32_t* list = lkeys;  // the un-pooled scores are no longer needed
       for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t cand = (prefix >> bit) | 1u;
-        uint32_t wcount = 0;
+        if (!compacted && U <= (uint32_t)NT) {
+          // open keys: existing positions whose bits above `bit` equal the prefix's
+          uint32_t my = 0;
 #pragma unroll
-        for (int j = 0; j < PER; ++j) wcount += __popcll(__ballot((rkeys[j] >> bit) == cand));
+          for (int j = 0; j < PER; ++j) {
+            const bool open = pos0 + 64 * j < npre && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
+            my += open ? 1u : 0u;
+          }
+          uint32_t total;
+          uint32_t off = block_inclusive_scan(my, hist, &total) - my;
+#pragma unroll
+          for (int j = 0; j < PER; ++j) {
+            const bool open = pos0 + 64 * j < npre && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
+            if (open) list[off++] = rkeys[j];
+          }
+          __syncthreads();
+          ck = (uint32_t)tid < total ? list[tid] : 0u;
+          G_list = G;
+          compacted = true;
+        }
+        const uint32_t cand = prefix | (1u << bit);
+        uint32_t wcount;
+        if (compacted) {
+          wcount = __popcll(__ballot(ck >= cand));
+        } else {
+          uint32_t cnt = 0;
+#pragma unroll
+          for (int j = 0; j < PER; ++j) cnt += (rkeys[j] >= cand) ? 1u : 0u;
+          wcount = 0;  // cnt <= 32: six bit planes
+#pragma unroll
+          for (int b = 0; b < 6; ++b) wcount += (uint32_t)__popcll(__ballot((cnt >> b) & 1u)) << b;
+        }
         uint32_t* slot = scan32 + ((bit & 1) ? NW : 0);  // two sets of per-wave slots: one barrier per bit
         if (lane == 0) slot[wave] = wcount;
         __syncthreads();
-        uint32_t c = 0;
+        uint32_t c = compacted ? G_list : 0u;
 #pragma unroll
         for (int w = 0; w < NW; ++w) c += slot[w];
-        if (c >= remaining) prefix |= 1u << bit;
-        else remaining -= c;
+        const bool take = c >= (uint32_t)kk;
+        if (!compacted) {
+          if (take) {
+            U = c - G;
+          } else {
+            U -= c - G;
+            G = c;
+          }
+        }
+        if (take) prefix = cand;
       }
     } else {
     uint32_t prefix_mask = 0;
@@ -205,10 +310,59 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       __syncthreads();
     }
     }
+    PKV_ST(3);
     const uint32_t T = prefix;           // bit pattern of the kk-th largest pooled score
-    const uint32_t need_eq = remaining;  // keys equal to T to take, lowest positions first (>= 1)
 
     // ---- C. ordered emission ----
+    if (LDSKEYS) {
+      // keys equal to T to take (lowest positions first) = kk - count(key > T); the counts per wave also give
+      // every wave the rank at which its range starts
+      uint32_t ngt = 0, neq = 0;  // per lane, at most 32 each
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        const bool ok = pos0 + 64 * j < npre;
+        ngt += (ok && rkeys[j] > T) ? 1u : 0u;
+        neq += (ok && rkeys[j] == T) ? 1u : 0u;
+      }
+      uint32_t cgt = 0, ceq = 0;
+#pragma unroll
+      for (int b = 0; b < 6; ++b) {
+        cgt += (uint32_t)__popcll(__ballot((ngt >> b) & 1u)) << b;
+        ceq += (uint32_t)__popcll(__ballot((neq >> b) & 1u)) << b;
+      }
+      if (lane == 0) {
+        hist[wave] = cgt;
+        hist[NW + wave] = ceq;
+      }
+      __syncthreads();
+      uint32_t gt_before = 0, eq_before = 0, gt_total = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const uint32_t g = hist[w], q = hist[NW + w];
+        gt_total += g;
+        if (w < wave) {
+          gt_before += g;
+          eq_before += q;
+        }
+      }
+      const uint32_t need_eq = (uint32_t)kk - gt_total;  // >= 1
+      const unsigned long long lt_mask = (1ull << lane) - 1ull;
+#pragma unroll
+      for (int j = 0; j < PER; ++j) {
+        const int i = pos0 + 64 * j;
+        const bool ok = i < npre;
+        const bool gt = ok && rkeys[j] > T, eq = ok && rkeys[j] == T;
+        const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+        if ((bgt | beq) == 0) continue;  // nothing kept among these 64 positions (the usual case)
+        const uint32_t gtb = gt_before + __popcll(bgt & lt_mask);
+        const uint32_t eqb = eq_before + __popcll(beq & lt_mask);
+        if (gt) idx[gtb + min(eqb, need_eq)] = i;
+        if (eq && eqb < need_eq) idx[gtb + eqb] = i;
+        gt_before += __popcll(bgt);
+        eq_before += __popcll(beq);
+      }
+    } else {
+    const uint32_t need_eq = remaining;  // keys equal to T to take, lowest positions first (>= 1)
     const int cw = ((npre + NW - 1) / NW + 63) & ~63;  // positions per wave, multiple of 64
     const int w0 = min(wave * cw, npre), w1 = min(w0 + cw, npre);
     uint32_t cgt = 0, ceq = 0;
@@ -242,8 +396,10 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       gt_before += __popcll(bgt);
       eq_before += __popcll(beq);
     }
+    }
   }
   for (int t = tid; t < alpha; t += NT) idx[kk + t] = npre + t;
+  PKV_ST(4);
 }
 
 __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatchArgs a) {
@@ -280,10 +436,10 @@ __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatch
   float* pooled = ly.pooled + (size_t)bg * a.N;
   if (npre <= kLdsKeys)
     select_unit<true>(raw, a.nrb, rb_stride, a.inv_G, pooled, ly.write_pooled != 0, idx, npre, kk, a.alpha, a.pool,
-                      a.pool_w, lkeys, tilebuf, hist, scan32, sel);
+                      a.pool_w, lkeys, tilebuf, hist, scan32, sel, a.dbg);
   else
     select_unit<false>(raw, a.nrb, rb_stride, a.inv_G, pooled, true, idx, npre, kk, a.alpha, a.pool, a.pool_w,
-                       lkeys, tilebuf, hist, scan32, sel);
+                       lkeys, tilebuf, hist, scan32, sel, a.dbg);
 }
 
 }  // namespace

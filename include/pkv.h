@@ -208,6 +208,24 @@ int pkv_compress_layers_profiled(
     size_t workspace_bytes, void* stream, void* const* events,
     int32_t n_events, int32_t* kernel_ids, int32_t* n_used);
 
+/*
+ * Measurement aid (no part of the method): streams `bytes` bytes starting at
+ * `buf` from memory once, with 16-byte loads by a grid that fills the chip,
+ * and discards them.  Timed by the caller (events or a synchronised clock), it
+ * gives the read bandwidth this device reaches on a plain scan: the measured
+ * ceiling beside the published peak in the roofline of the scoring kernel.
+ *
+ * buf    DEVICE pointer, 16-byte aligned, readable for `bytes` bytes.
+ * bytes  multiple of 16, > 0.
+ * sink   DEVICE uint32, written only if a checksum of the data takes one
+ *        particular value (it keeps the loads alive); contents meaningless.
+ * stream hipStream_t as void*.  Asynchronous; never allocates.
+ * Returns PKV_OK, PKV_ERR_INVALID_ARG (null / misaligned / size) or
+ * PKV_ERR_HIP.
+ */
+int pkv_probe_read(const void* buf, size_t bytes, uint32_t* sink,
+                   void* stream);
+
 /* Static, NUL-terminated description of a pkv_status value.  HOST only. */
 const char* pkv_status_string(int status);
 

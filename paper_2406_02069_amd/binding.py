@@ -20,7 +20,7 @@ POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers",
-           "pkv_compress_layers_profiled", "pkv_status_string"]
+           "pkv_compress_layers_profiled", "pkv_probe_read", "pkv_status_string"]
 
 
 class PkvError(RuntimeError):
@@ -183,6 +183,17 @@ class LayersCall:
 def compress_layers(Q_win, K, V, k_ls, pool, pool_w, seq_lens=None, want_scores=False):
     """pkv_compress_layers: all layers of one request batch.  Returns a list of per-layer output tuples."""
     return LayersCall(Q_win, K, V, k_ls, pool, pool_w, seq_lens, want_scores).run()
+
+
+def probe_read(buf: torch.Tensor, sink: torch.Tensor) -> None:
+    """pkv_probe_read: one streaming read of `buf` (contiguous, 16-byte multiple) on the current stream."""
+    lib = load()
+    lib.pkv_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    lib.pkv_probe_read.restype = ctypes.c_int
+    assert buf.is_contiguous() and sink.dtype == torch.int32
+    rc = lib.pkv_probe_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream_ptr(buf.device))
+    if rc != OK:
+        raise PkvError(rc, "pkv_probe_read")
 
 
 KERNEL_NAMES = ["score_stats", "score_finalize", "score_accum", "pool_select", "gather", "score_resident"]

@@ -382,6 +382,11 @@ int pkv_compress_layers_profiled(int32_t L, const pkv_layer_desc* descs, const v
   return rc;
 }
 
+int pkv_probe_read(const void* buf, size_t bytes, uint32_t* sink, void* stream) {
+  if (!buf || !sink || bytes == 0 || bytes % 16 != 0 || ((uintptr_t)buf & 15) || ((uintptr_t)sink & 3)) return PKV_ERR_INVALID_ARG;
+  return launch_probe_read(buf, bytes, sink, static_cast<hipStream_t>(stream)) == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
 const char* pkv_status_string(int status) {
   switch (status) {
     case PKV_OK: return "ok";

@@ -32,7 +32,26 @@ __global__ __launch_bounds__(256) void gather_batch_kernel(const GatherBatchArgs
   *reinterpret_cast<uint4*>(ly.V_out + o) = vv;
 }
 
+// Plain streaming read (bandwidth probe): every lane folds its 16-byte words into a checksum.
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict__ p, size_t n16, uint32_t* sink) {
+  uint32_t acc = 0;
+  const size_t stride = (size_t)gridDim.x * 256 * 4;
+  for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i < n16; i += stride) {
+    uint4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = (i + 256 * k < n16) ? p[i + 256 * k] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+  }
+  if (acc == 0x9E3779B9u) *sink = acc;
+}
+
 }  // namespace
+
+hipError_t launch_probe_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s) {
+  hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 8), dim3(256), 0, s, static_cast<const uint4*>(buf), bytes / 16, sink);
+  return hipGetLastError();
+}
 
 hipError_t launch_gather_batch(const GatherBatchArgs& a, hipStream_t s) {
   const int lpr = a.d / 8;

@@ -132,6 +132,7 @@ struct GatherBatchArgs {
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s);
 hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipStream_t s);
 hipError_t launch_gather_batch(const GatherBatchArgs& a, hipStream_t s);
+hipError_t launch_probe_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s);
 
 // Each returns hipSuccess or the launch error.
 hipError_t launch_score_stats(const ScoreArgs& a, hipStream_t s);

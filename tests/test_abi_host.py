@@ -118,3 +118,14 @@ def test_compress_layers_rejects_mismatched_layers():
     assert rc == binding.ERR_INVALID_ARG
     rc = lib.pkv_compress_layers(0, descs, arr, arr, arr, None, arr, arr, arr, arr, None, 0x10000, 1 << 30, None)
     assert rc == binding.ERR_INVALID_ARG
+
+
+def test_probe_read_rejects_bad_arguments_before_any_launch():
+    lib = binding.load()
+    lib.pkv_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    lib.pkv_probe_read.restype = ctypes.c_int
+    assert lib.pkv_probe_read(None, 1024, 0x1000, None) == binding.ERR_INVALID_ARG      # no buffer
+    assert lib.pkv_probe_read(0x1000, 1024, None, None) == binding.ERR_INVALID_ARG      # no sink
+    assert lib.pkv_probe_read(0x1000, 0, 0x2000, None) == binding.ERR_INVALID_ARG       # empty
+    assert lib.pkv_probe_read(0x1000, 1000, 0x2000, None) == binding.ERR_INVALID_ARG    # not a multiple of 16
+    assert lib.pkv_probe_read(0x1008, 1024, 0x2000, None) == binding.ERR_INVALID_ARG    # misaligned buffer

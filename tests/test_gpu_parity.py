@@ -209,3 +209,28 @@ def test_non_finite_inputs_stay_in_bounds(score_path):
             if (b, g) != (0, 0):
                 assert np.array_equal(row, clean[2][b, g].cpu().numpy()), (b, g)
                 assert torch.equal(out[4][b, g], clean[4][b, g])
+
+
+def test_probe_read_runs_and_leaves_the_buffer_alone():
+    x = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
+    ref = x.clone()
+    sink = torch.zeros(1, dtype=torch.int32, device=DEV)
+    for n in (1 << 20, 4, 4096 + 4):                       # whole buffer, one 16-byte word, a ragged tail of the grid
+        binding.probe_read(x[:n], sink)
+    torch.cuda.synchronize()
+    assert torch.equal(x, ref)
+
+
+def test_all_layers_without_score_output_keep_the_same_tokens():
+    # the benchmark's launch shape: one call over every layer, pooled scores kept in the workspace only
+    w = synth.WORKLOADS[2].scaled(N=6000, L=5)
+    layers = [synth.make_layer(w, l, DEV) for l in range(w.L)]
+    Qs, Ks, Vs = [x[0] for x in layers], [x[1] for x in layers], [x[2] for x in layers]
+    ks = binding.budgets(w.L, 128, w.beta, w.alpha)
+    with_scores = binding.compress_layers(Qs, Ks, Vs, ks, w.pool, w.pool_w, want_scores=True)
+    without = binding.compress_layers(Qs, Ks, Vs, ks, w.pool, w.pool_w, want_scores=False)
+    torch.cuda.synchronize()
+    for a, b in zip(with_scores, without):
+        assert b[4] is None
+        for x, y in zip(a[:4], b[:4]):
+            assert torch.equal(x, y)

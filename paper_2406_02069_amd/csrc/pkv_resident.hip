@@ -463,6 +463,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       } else {
         for (int r = lane; r < 2 * kRowBlock; r += 64) stat[wave][r >> 7][r & 127] = make_float2(-INFINITY, 0.f);
       }
+      // From here to the start of sweep 2 the wave has little to issue and most of it sits on the critical path of
+      // the whole group (statistics, arrival, fold, release): it goes first at the issue port that it shares with
+      // a wave of another group that is in the middle of a sweep.
+      __builtin_amdgcn_s_setprio(3);
       __syncthreads();
       if (tid < rows_here) {
         float m = -INFINITY, z = 0.f;
@@ -567,6 +571,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       }
       __syncthreads();
     }
+    __builtin_amdgcn_s_setprio(0);
     PKV_T(2);
     PKV_TN(4);
 

@@ -77,8 +77,8 @@ def cpu_baseline(w, ks, layers_host, lens, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: the 32k config)")
     ap.add_argument("--avg-budget", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -132,7 +132,13 @@ size_t pkv_workspace_bytes(const pkv_layer_desc* desc, int32_t L);
  * idx_out    DEVICE int32 [B,Hkv,k_cap] contiguous, written: kept positions,
  *            ascending; the last min(alpha,n_b) valid entries are the window;
  *            entries >= count are -1.
- * count_out  DEVICE int32 [B], written: min(k_l, n_b).
+ * count_out  DEVICE int32 [B], written: min(k_l, n_b); or -1 for every
+ *            sequence if the scoring kernel had to give up a wait between
+ *            its workgroups (they exchange softmax statistics and rely on
+ *            being resident on the device together; another tenant of the
+ *            device can prevent that).  Every wait is bounded, so the call
+ *            always completes; with count -1 the other outputs of the call
+ *            are in range but meaningless and the call should be repeated.
  * scores_out DEVICE fp32 [B,Hkv,N] contiguous, or NULL: pooled scores before
  *            selection, defined for i < n_b-alpha when k_l < n_b; other
  *            entries are left untouched.

@@ -51,8 +51,8 @@ Plan make_plan(const pkv_layer_desc& d, int L) {
   const size_t raw_str = U * p.nrb * d.N * sizeof(float);
   size_t off = 0;
   p.off_cnt = off;
-  // [U counters][error word][pad to 8 bytes][nslots * Rpad tagged normaliser words]
-  p.sync_bytes = ((U + 1) * sizeof(int32_t) + 7) / 8 * 8 + nslots * p.res_Rpad * sizeof(uint64_t);
+  // [error word, 8 bytes][U counters][pad to 8 bytes][nslots * Rpad tagged normaliser words]
+  p.sync_bytes = 8 + (U * sizeof(int32_t) + 7) / 8 * 8 + nslots * p.res_Rpad * sizeof(uint64_t);
   off += align256(p.sync_bytes);
   p.off_part = off;
   off += align256(part_res > part_str ? part_res : part_str);
@@ -147,6 +147,12 @@ static int resident_stagger() {
   return 250;
 }
 
+// Probes before a workgroup gives up waiting for its group (about 2 s; test hook: PKV_SPIN_LIMIT).
+static int resident_spin_limit() {
+  if (const char* e = getenv("PKV_SPIN_LIMIT")) return atoi(e);
+  return 1 << 20;
+}
+
 static bool use_resident(const Plan& plan) {
   if (const char* e = getenv("PKV_SCORE_PATH")) {  // test hook: "stream" forces the per-layer kernels
     if (!strcmp(e, "stream")) return false;
@@ -182,16 +188,20 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       ra.U = nl * plan.BH;
       ra.raw = raw + (size_t)l0 * plan.BH * d.N;
       ra.part = reinterpret_cast<float2*>(ws + plan.off_part);
-      ra.cnt = reinterpret_cast<int32_t*>(ws + plan.off_cnt);
-      ra.err = ra.cnt + ra.U;
-      const size_t cbuf_off = ((size_t)(ra.U + 1) * sizeof(int32_t) + 7) / 8 * 8;
+      // the error word is cleared by the first launch of the call only: a later launch must not hide an earlier give-up
+      ra.err = reinterpret_cast<int32_t*>(ws + plan.off_cnt);
+      ra.cnt = ra.err + 2;
+      const size_t cbuf_off = 8 + ((size_t)ra.U * sizeof(int32_t) + 7) / 8 * 8;
       ra.cbuf = reinterpret_cast<unsigned long long*>(ws + plan.off_cnt + cbuf_off);
-      ra.sync_words = (int32_t)((cbuf_off + (size_t)plan.ngroups * plan.UPG * plan.res_Rpad * sizeof(uint64_t)) / 4);
+      const int32_t all_words = (int32_t)((cbuf_off + (size_t)plan.ngroups * plan.UPG * plan.res_Rpad * sizeof(uint64_t)) / 4);
+      ra.zero_base = l0 == 0 ? ra.err : ra.cnt;
+      ra.sync_words = l0 == 0 ? all_words : all_words - 2;
       ra.dbg = reinterpret_cast<long long*>(ws + plan.off_dbg);
       ra.L = nl; ra.B = d.B; ra.Hq = d.Hq; ra.Hkv = d.Hkv; ra.G = plan.G; ra.alpha = d.alpha; ra.N = d.N;
       ra.R = plan.R; ra.Rpad = plan.res_Rpad; ra.nrb = plan.res_nrb; ra.TPU = plan.TPU;
       ra.ngroups = plan.ngroups; ra.UPG = plan.UPG;
       ra.stagger = resident_stagger();
+      ra.spin_limit = resident_spin_limit();
       ra.d = d.d;
       ra.q_sb = d.q_sb; ra.q_sh = d.q_sh; ra.q_st = d.q_st;
       ra.kv_sb = d.kv_sb; ra.kv_sh = d.kv_sh; ra.kv_st = d.kv_st;
@@ -262,6 +272,8 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
     se.nrb = nrb;
     se.inv_G = resident ? 1.0f : 1.0f / (float)plan.G;
     se.dbg = reinterpret_cast<long long*>(ws + plan.off_dbg) + kResidentGrid * 16 + 1024;
+    // the error word of this call's scoring launches
+    se.err = (any_scores && resident) ? reinterpret_cast<const int32_t*>(ws + plan.off_cnt) : nullptr;
     ga.L = nl; ga.B = d.B; ga.Hkv = d.Hkv; ga.d = d.d; ga.k_cap_max = k_cap_max; ga.N = d.N;
     ga.kv_sb = d.kv_sb; ga.kv_sh = d.kv_sh; ga.kv_st = d.kv_st;
     if (launch_pool_select_batch(se, nl, stream) != hipSuccess) return PKV_ERR_HIP;

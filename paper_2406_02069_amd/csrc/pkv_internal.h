@@ -40,7 +40,7 @@ struct Plan {
   int nchunk;    // ceil(N / KC)
   // workspace carve-up (byte offsets, each 256-aligned)
   size_t off_cnt, off_part, off_cfin, off_raw, off_pooled, off_dbg, total;
-  size_t sync_bytes;  // counters + error word + tagged normalisers (zeroed before each resident launch)
+  size_t sync_bytes;  // error word + counters + tagged normalisers (zeroed before each resident launch)
 };
 
 Plan make_plan(const pkv_layer_desc& d, int L);
@@ -77,15 +77,17 @@ struct ResidentArgs {
   const int32_t* seq_lens;
   float* raw;     // [U][N] un-pooled scores
   float2* part;   // [nslots][TPU][Rpad] per-part softmax statistics (log2 domain), reused from unit to unit
-  int32_t* cnt;   // [U] arrivals per unit; start of the zeroed synchronisation words
-  int32_t* err;   // == cnt + U: set to 1 if a bounded wait gave up
+  int32_t* cnt;   // [U] arrivals per unit
+  int32_t* err;   // in front of cnt: set to 1 if a bounded wait gave up; cleared by the first launch of a call only
+  int32_t* zero_base;  // start of the words to zero before the launch (err or cnt)
   unsigned long long* cbuf;  // [nslots][Rpad] (unit tag << 32 | normaliser bits), behind err, 8-byte aligned
   long long* dbg; // per-workgroup phase timers (development builds only), may be null
-  int32_t sync_words;  // 32-bit words to zero before the launch: counters, error word, cbuf
+  int32_t sync_words;  // 32-bit words to zero from zero_base: (error word,) counters, cbuf
   int32_t L, B, Hq, Hkv, G, alpha, N, R, Rpad, nrb, TPU, U, d;
   int32_t ngroups;  // independent groups of workgroups: 512 / group size
   int32_t UPG;      // units a group works on at the same time: group size / TPU
   int32_t stagger;  // start offset between consecutive groups, in 10 ns ticks
+  int32_t spin_limit;  // probes of a tagged word before a workgroup gives up waiting and raises the error word
   int64_t q_sb, q_sh, q_st, kv_sb, kv_sh, kv_st;
   float kappa, inv_kappa, inv_G;
 };
@@ -110,6 +112,7 @@ struct SelectBatchArgs {
   int32_t nrb;         // partial score arrays to add per layer
   float inv_G;         // factor applied to the sum of the partials
   long long* dbg;      // per-unit phase timers (development builds only), may be null
+  const int32_t* err;  // error word of the scoring kernel (non-zero: a wait was given up), or null
 };
 
 struct GatherLayer {

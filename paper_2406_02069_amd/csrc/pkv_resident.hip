@@ -57,7 +57,6 @@ constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int kTiles = 4;          // 32-key tiles held by one wave
 constexpr int kRowBlock = 128;     // rows of Q staged in LDS at a time
-constexpr int kSpinLimit = 1 << 20;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
@@ -560,7 +559,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
             w = ld64(&cbuf[r]);
             if ((unsigned)(w >> 32) == tag) break;
             __builtin_amdgcn_s_sleep(1);
-            if (++spins > kSpinLimit || ((spins & 1023) == 0 && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+            if (++spins > a.spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
               __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               break;
             }
@@ -732,7 +731,7 @@ static hipError_t launch_resident(const ResidentArgs& a, hipStream_t s) {
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s) {
   // the counters, the error word and the tagged normaliser words must start at zero
   const int nz = a.sync_words;
-  hipLaunchKernelGGL(zero_kernel, dim3((nz + 255) / 256), dim3(256), 0, s, a.cnt, nz);
+  hipLaunchKernelGGL(zero_kernel, dim3((nz + 255) / 256), dim3(256), 0, s, a.zero_base, nz);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.d == 128) return launch_resident<128>(a, s);

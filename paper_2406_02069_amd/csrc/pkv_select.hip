@@ -423,7 +423,8 @@ __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatch
     n = n < 0 ? 0 : (n > a.N ? a.N : n);
   }
   const int count = ly.k_l < n ? ly.k_l : n;
-  if (g == 0 && tid == 0) ly.count_out[b] = count;
+  // a scoring kernel that gave up a wait leaves meaningless scores: the caller learns it from the count
+  if (g == 0 && tid == 0) ly.count_out[b] = (a.err && *a.err != 0) ? -1 : count;
   int32_t* idx = ly.idx_out + (size_t)bg * ly.k_cap;
   if (ly.k_l >= n) {  // keep everything
     for (int j = tid; j < ly.k_cap; j += NT) idx[j] = j < n ? j : -1;

@@ -107,6 +107,15 @@ __device__ __forceinline__ int fresh(int v) {
   return v;
 }
 
+// Workgroup barrier that orders LDS traffic only.  A full __syncthreads() also waits until every global store of
+// the wave has been acknowledged, and with it, since memory operations retire in order, for every key load that
+// was requested in between: exactly the loads that are meant to stay in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ __forceinline__ void st64(u64* p, u64 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ u64 ld64(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
@@ -233,7 +242,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       }
       qoff[tid] = off;
     }
-    __syncthreads();
+    lds_barrier();
     const char* src = reinterpret_cast<const char*>(d.Q) + q_seg * 16;
     u32x4 v[QLD];
 #pragma unroll
@@ -466,7 +475,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       // the whole group (statistics, arrival, fold, release): it goes first at the issue port that it shares with
       // a wave of another group that is in the middle of a sweep.
       __builtin_amdgcn_s_setprio(3);
-      __syncthreads();
+      lds_barrier();
       if (tid < rows_here) {
         float m = -INFINITY, z = 0.f;
 #pragma unroll
@@ -526,7 +535,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
           }
         }
         red[q * kRowBlock + rl] = make_float2(m, z);
-        __syncthreads();
+        lds_barrier();
         if (q == 0) {
 #pragma unroll
           for (int k = 1; k < NQ; ++k) merge_stats(m, z, red[k * kRowBlock + rl].x, red[k * kRowBlock + rl].y);
@@ -535,7 +544,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
           cfr[r] = split3(c);
           if (r < a.R) st64(&cbuf[r], ((u64)tag << 32) | __float_as_uint(c));
         }
-        __syncthreads();
+        lds_barrier();
       }
 #ifdef PKV_RES_TIMING
       tstamp[3] += wall_clock64();
@@ -568,7 +577,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         }
         cfr[r] = split3(c);
       }
-      __syncthreads();
+      lds_barrier();
     }
     __builtin_amdgcn_s_setprio(0);
     PKV_T(2);
@@ -693,7 +702,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     for (int rb = 0; rb + 1 < a.nrb; ++rb) s2_block(rb, std::false_type{});
     s2_block(a.nrb - 1, std::true_type{});
     if (has_next && !q_staged) stage_q(nxt_u, 0, qsmem + (buf ^ 1) * QBUF);
-    __syncthreads();  // cfr / stat and the Q buffers change hands
+    lds_barrier();  // cfr / stat and the Q buffers change hands
     PKV_T(4);
     cur_u = nxt_u;
     buf ^= 1;

@@ -257,3 +257,21 @@ def test_given_up_wait_is_reported_through_the_counts(monkeypatch):
     for l, out in enumerate(good):
         assert out[3].cpu().tolist() == [min(ks[l], w.N)] * w.B
         compare_layer(Qs[l], Ks[l], Vs[l], ks[l], w.alpha, w.pool, w.pool_w, None, out)
+
+
+def test_more_layers_than_one_launch_holds(score_path):
+    # 100 layers: the kernel-argument tables hold 96 (scoring) and 40 (select, gather) layers per launch, so the
+    # call is split into several launches that share one workspace.
+    L, alpha, N = 100, 8, 700
+    w = _W(alpha, synth.POOL_MAX, 7)
+    layers = [_rand(1, 8, 2, 64, N, alpha, seed=1000 + l) for l in range(L)]
+    Qs, Ks, Vs = [x[0] for x in layers], [x[1] for x in layers], [x[2] for x in layers]
+    ks = [alpha + 1 + (l * 7) % 90 for l in range(L)]
+    outs = binding.compress_layers(Qs, Ks, Vs, ks, w.pool, w.pool_w, want_scores=True)
+    torch.cuda.synchronize()
+    for l in (0, 39, 40, 79, 80, 95, 96, 99):
+        single = binding.compress_layer(Qs[l], Ks[l], Vs[l], ks[l], w.pool, w.pool_w, want_scores=True)
+        torch.cuda.synchronize()
+        for x, y in zip(outs[l], single):
+            assert torch.equal(x, y), l
+    compare_layer(Qs[96], Ks[96], Vs[96], ks[96], alpha, w.pool, w.pool_w, None, outs[96])

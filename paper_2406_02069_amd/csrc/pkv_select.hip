@@ -10,8 +10,8 @@
 //      fp32 bit patterns are the selection keys (scores are >= 0, so unsigned order = numeric order).
 //   B. the kk-th largest key T.  Keys in registers: binary search on T, one bit per round from the top; a
 //      round counts the keys >= the candidate (per lane, then per wave through ballots, then 16 wave counts
-//      through LDS: one barrier, no atomics).  As soon as at most 1024 keys still agree with the decided
-//      bits, those keys move to a list and the remaining rounds look at one key per thread.
+//      through LDS: one barrier, no atomics).  As soon as at most 512 keys still agree with the decided
+//      bits, those keys move to a list and one wave decides the remaining bits on its own.
 //      Keys in global memory: radix select, three digit levels (11 + 11 + 10 bits) with LDS histograms.
 //   C. ordered emission: every wave owns a contiguous range of positions; ballots give each kept key
 //      its rank, so positions with key > T, and the lowest positions with key == T, come out in
@@ -210,69 +210,77 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
     uint32_t remaining = (uint32_t)kk;
     if (LDSKEYS) {
       // Keys sit in registers: binary search for the largest T with count(key >= T) >= kk, one bit per round
-      // from the top.  Per round every lane counts its own keys, the wave adds the lane counts up (ballots over
-      // the bits of the count: no LDS atomics, nothing that depends on timing) and the 16 wave counts meet in LDS:
-      // one barrier per bit.  All 32 bits are searched although scores are >= 0: whatever bit patterns the scores
+      // from the top.  Per round every wave counts its keys (ballots and scalar pop-counts: no LDS atomics,
+      // nothing that depends on timing) and the 16 wave counts meet in LDS: one barrier per bit.  All 32 bits are searched although scores are >= 0: whatever bit patterns the scores
       // hold (NaN, negative zero), exactly kk positions are selected.  Positions that do not exist carry key 0
       // and are never counted (T >= 1 in every comparison).
       //
       // Bookkeeping that comes for free: U = number of keys that still agree with the decided bits (the only
-      // ones whose comparison is open), G = number of keys above all of them.  Once U fits one key per thread
-      // the open keys are moved to a list in LDS and the remaining rounds compare one key per thread.
+      // ones whose comparison is open), G = number of keys above all of them.  Once U is at most 512
+      // the open keys are moved to a list in LDS and a single wave decides the remaining bits on its own.
       uint32_t U = (uint32_t)npre, G = 0;
-      uint32_t G_list = 0;  // keys above every key of the list (fixed once the list exists)
-      bool compacted = false;
-      uint32_t ck = 0;  // the thread's key after compaction
       uint32_t* list = lkeys;  // the un-pooled scores are no longer needed
-      for (int bit = 31; bit >= 0; --bit) {
-        if (!compacted && U <= (uint32_t)NT) {
-          // open keys: existing positions whose bits above `bit` equal the prefix's
-          uint32_t my = 0;
-#pragma unroll
-          for (int j = 0; j < PER; ++j) {
-            const bool open = pos0 + 64 * j < npre && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
-            my += open ? 1u : 0u;
-          }
-          uint32_t total;
-          uint32_t off = block_inclusive_scan(my, hist, &total) - my;
-#pragma unroll
-          for (int j = 0; j < PER; ++j) {
-            const bool open = pos0 + 64 * j < npre && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
-            if (open) list[off++] = rkeys[j];
-          }
-          __syncthreads();
-          ck = (uint32_t)tid < total ? list[tid] : 0u;
-          G_list = G;
-          compacted = true;
-        }
+      int bit = 31;
+      // rounds over all keys, until few enough are open
+      constexpr int kList = 512;  // open keys that the finishing wave can hold (8 per lane)
+      for (; bit >= 0 && U > (uint32_t)kList; --bit) {
         const uint32_t cand = prefix | (1u << bit);
-        uint32_t wcount;
-        if (compacted) {
-          wcount = __popcll(__ballot(ck >= cand));
-        } else {
-          uint32_t cnt = 0;
+        uint32_t wcount = 0;  // ballot + scalar pop-count per key: the scalar unit counts while the vector unit compares
 #pragma unroll
-          for (int j = 0; j < PER; ++j) cnt += (rkeys[j] >= cand) ? 1u : 0u;
-          wcount = 0;  // cnt <= 32: six bit planes
-#pragma unroll
-          for (int b = 0; b < 6; ++b) wcount += (uint32_t)__popcll(__ballot((cnt >> b) & 1u)) << b;
-        }
+        for (int j = 0; j < PER; ++j) wcount += __popcll(__ballot(rkeys[j] >= cand));
         uint32_t* slot = scan32 + ((bit & 1) ? NW : 0);  // two sets of per-wave slots: one barrier per bit
         if (lane == 0) slot[wave] = wcount;
         __syncthreads();
-        uint32_t c = compacted ? G_list : 0u;
+        uint32_t c = 0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) c += slot[w];
-        const bool take = c >= (uint32_t)kk;
-        if (!compacted) {
-          if (take) {
-            U = c - G;
-          } else {
-            U -= c - G;
-            G = c;
-          }
+        if (c >= (uint32_t)kk) {
+          prefix = cand;
+          U = c - G;
+        } else {
+          U -= c - G;
+          G = c;
         }
-        if (take) prefix = cand;
+      }
+      if (bit >= 0) {
+        // the open keys (existing positions whose bits above `bit` equal the prefix's) move to a list in LDS ...
+        uint32_t my = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+          const bool open = pos0 + 64 * j < npre && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
+          my += open ? 1u : 0u;
+        }
+        uint32_t total;
+        uint32_t off = block_inclusive_scan(my, hist, &total) - my;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+          const bool open = pos0 + 64 * j < npre && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
+          if (open) list[off++] = rkeys[j];
+        }
+        __syncthreads();
+#ifdef PKV_SEL_TIMING
+        if (threadIdx.x == 0 && blockIdx.x < 256 && g_dbg) { g_dbg[blockIdx.x * 8 + 5] = clock64(); g_dbg[blockIdx.x * 8 + 6] = bit; }
+#endif
+        // ... and one wave finishes the search on them alone: 8 keys per lane, no barrier between the rounds
+        if (wave == 0) {
+          constexpr int LK = kList / 64;
+          uint32_t lk[LK];
+#pragma unroll
+          for (int i = 0; i < LK; ++i) lk[i] = (uint32_t)(lane + 64 * i) < total ? list[lane + 64 * i] : 0u;
+          for (; bit >= 0; --bit) {
+            const uint32_t cand = prefix | (1u << bit);
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int i = 0; i < LK; ++i) cnt += (lk[i] >= cand) ? 1u : 0u;
+            uint32_t c = G;  // keys above every key of the list
+#pragma unroll
+            for (int b = 0; b < 4; ++b) c += (uint32_t)__popcll(__ballot((cnt >> b) & 1u)) << b;  // cnt <= 8
+            if (c >= (uint32_t)kk) prefix = cand;
+          }
+          if (lane == 0) sel[0] = prefix;
+        }
+        __syncthreads();
+        prefix = sel[0];
       }
     } else {
     uint32_t prefix_mask = 0;

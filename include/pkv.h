@@ -24,6 +24,12 @@
  *    allocate or free memory.  Results are deterministic: the same inputs
  *    give bit-identical outputs.
  *  - Inputs are never modified.
+ *  - Environment variables read at call time (tuning and test hooks; none is
+ *    needed in production): PKV_SCORE_PATH=stream forces the per-layer
+ *    scoring kernels that read K twice instead of the register-resident one;
+ *    PKV_STAGGER=<ticks of 10 ns> sets the start offset between workgroup
+ *    groups of the resident kernel; PKV_SPIN_LIMIT=<probes> bounds its
+ *    waits (0: give up at once, which a test uses to see count_out = -1).
  */
 #ifndef PKV_H_
 #define PKV_H_

@@ -77,6 +77,9 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
   const bool is_max = pool == PKV_POOL_MAX;
   const float inv_w = 1.0f / (float)pool_w;
   const int pos0 = wave * CW + lane;   // the thread's first position; the others follow in steps of 64
+  // number of the thread's positions that exist (position pos0 + 64 * j exists iff j < nval): one register instead
+  // of 32 position registers kept alive for the comparisons
+  const int nval = min(max((npre - pos0 + 63) >> 6, 0), kLdsKeys / NT);
   if (LDSKEYS) {
     // The whole prefix fits in LDS: every load of the un-pooled scores is in flight at once (one memory round
     // trip), then each thread pools its positions out of LDS; the pooled values stay in registers, already in
@@ -84,11 +87,9 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
     float* lsc = reinterpret_cast<float*>(lkeys);
     float v[PER];
     if (nrb == 1) {
+      const float* rp = raw + pos0;
 #pragma unroll
-      for (int j = 0; j < PER; ++j) {
-        const int i = pos0 + 64 * j;
-        v[j] = (i < npre) ? raw[i] : 0.f;
-      }
+      for (int j = 0; j < PER; ++j) v[j] = (j < nval) ? rp[64 * j] : 0.f;
     } else {
 #pragma unroll
       for (int j = 0; j < PER; ++j) {
@@ -99,11 +100,13 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
         v[j] = sacc;
       }
     }
+    {
+      float* lp = lsc + pos0;
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
-      const int i = pos0 + 64 * j;
-      v[j] *= inv_G;
-      if (i < npre) lsc[i] = v[j];
+      for (int j = 0; j < PER; ++j) {
+        v[j] *= inv_G;
+        if (j < nval) lp[64 * j] = v[j];
+      }
     }
     __syncthreads();
     PKV_ST(1);
@@ -133,7 +136,7 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
             if (mx) acc = ok ? fmaxf(acc, x) : acc;
             else acc += ok ? x : 0.f;
           }
-          if (i < npre) v[j] = mx ? acc : acc * inv_w;
+          if (j < nval) v[j] = mx ? acc : acc * inv_w;
         }
       }
     };
@@ -161,14 +164,13 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       }
     }
     if (write_pooled) {
+      float* pp = pooled + pos0;
 #pragma unroll
-      for (int j = 0; j < PER; ++j) {
-        const int i = pos0 + 64 * j;
-        if (i < npre) pooled[i] = v[j];
-      }
+      for (int j = 0; j < PER; ++j)
+        if (j < nval) pp[64 * j] = v[j];
     }
 #pragma unroll
-    for (int j = 0; j < PER; ++j) rkeys[j] = (pos0 + 64 * j < npre) ? __float_as_uint(v[j]) : 0u;
+    for (int j = 0; j < PER; ++j) rkeys[j] = (j < nval) ? __float_as_uint(v[j]) : 0u;
     PKV_ST(2);
   } else {
     for (int t0 = 0; t0 < npre; t0 += TS) {
@@ -247,14 +249,14 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
         uint32_t my = 0;
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
-          const bool open = pos0 + 64 * j < npre && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
+          const bool open = j < nval && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
           my += open ? 1u : 0u;
         }
         uint32_t total;
         uint32_t off = block_inclusive_scan(my, hist, &total) - my;
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
-          const bool open = pos0 + 64 * j < npre && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
+          const bool open = j < nval && (bit == 31 || (rkeys[j] >> (bit + 1)) == (prefix >> (bit + 1)));
           if (open) list[off++] = rkeys[j];
         }
         __syncthreads();
@@ -328,7 +330,7 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       uint32_t ngt = 0, neq = 0;  // per lane, at most 32 each
 #pragma unroll
       for (int j = 0; j < PER; ++j) {
-        const bool ok = pos0 + 64 * j < npre;
+        const bool ok = j < nval;
         ngt += (ok && rkeys[j] > T) ? 1u : 0u;
         neq += (ok && rkeys[j] == T) ? 1u : 0u;
       }
@@ -357,13 +359,13 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       const unsigned long long lt_mask = (1ull << lane) - 1ull;
 #pragma unroll
       for (int j = 0; j < PER; ++j) {
-        const int i = pos0 + 64 * j;
-        const bool ok = i < npre;
+        const bool ok = j < nval;
         const bool gt = ok && rkeys[j] > T, eq = ok && rkeys[j] == T;
         const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
         if ((bgt | beq) == 0) continue;  // nothing kept among these 64 positions (the usual case)
         const uint32_t gtb = gt_before + __popcll(bgt & lt_mask);
         const uint32_t eqb = eq_before + __popcll(beq & lt_mask);
+        const int i = pos0 + 64 * j;
         if (gt) idx[gtb + min(eqb, need_eq)] = i;
         if (eq && eqb < need_eq) idx[gtb + eqb] = i;
         gt_before += __popcll(bgt);

@@ -375,8 +375,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
                         int rt_next, float& m, float& z) {
           constexpr int tc = decltype(TC)::value, tn = decltype(TN)::value;
           constexpr bool issue = decltype(ISSUE)::value;  // false: the pass ends here, no further product
-          if (dirty_mask & (1 << tc)) {
-            // slow variant (masks, exact update); the next product is still issued first
+          const bool dirty = (dirty_mask & (1 << tc)) != 0;
+          if (dirty && decltype(FIRST)::value) {
+            // A masked tile that also has to found the lane's reference exponent (no earlier tile of the wave in
+            // this unit): exact running-maximum update; the next product is still issued first.
             nxt = zero16;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -386,30 +388,42 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
             refill(ru, RFT, HALF);
             exact_update(cur, tc, true, lim_rel_of(rt), m, z);
           } else {
-            if (decltype(FIRST)::value) {  // provisional reference: the largest of three of the lane's logits
-              m = a.kappa * fmaxf(fmaxf(cur[0], cur[5]), cur[10]);
-              z = 0.f;
-            }
-            const float nref = -m;
-            float s0 = 0.f, s1 = 0.f;
-            nxt = zero16;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-              if (issue) nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
-              if (decltype(RELOAD)::value) qf[ks] = q_frag(rt_next, ks);  // last use of this fragment was the MFMA above
-              float x[TPM], e[TPM];
-#pragma unroll
-              for (int j = 0; j < TPM; ++j) x[j] = __builtin_fmaf(cur[TPM * ks + j], a.kappa, nref);
-#pragma unroll
-              for (int j = 0; j < TPM; ++j) e[j] = fast_exp2(x[j]);
-#pragma unroll
-              for (int j = 0; j < TPM; ++j) {
-                if (j & 1) s1 += e[j]; else s0 += e[j];
+            // The pipelined variant; MASKED: the tile reaches beyond the prefix (causal window, end of the
+            // sequence), logits of keys the lane's query does not see become -inf before the exponential.  The
+            // reference exponent then comes from an earlier, unmasked tile of the wave.
+            auto fast = [&](auto MASKED) {
+              constexpr bool masked = decltype(MASKED)::value;
+              if (decltype(FIRST)::value) {  // provisional reference: the largest of three of the lane's logits
+                m = a.kappa * fmaxf(fmaxf(cur[0], cur[5]), cur[10]);
+                z = 0.f;
               }
-              PKV_CHUNK_END_SUMS(s0, s1);
-              if (ks == KS / 2 - 1) refill(ru, RFT, HALF);
-            }
-            z += s0 + s1;
+              const float nref = -m;
+              const int lim = masked ? lim_rel_of(rt) - 32 * tc : 0;  // last visible key, relative to this tile and half
+              float s0 = 0.f, s1 = 0.f;
+              nxt = zero16;
+#pragma unroll
+              for (int ks = 0; ks < KS; ++ks) {
+                if (issue) nxt = PKV_MFMA32(kf[tn][ks], qf[ks], nxt);
+                if (decltype(RELOAD)::value) qf[ks] = q_frag(rt_next, ks);  // last use of this fragment was the MFMA above
+                float x[TPM], e[TPM];
+#pragma unroll
+                for (int j = 0; j < TPM; ++j) {
+                  x[j] = __builtin_fmaf(cur[TPM * ks + j], a.kappa, nref);
+                  if (masked && mrow0(TPM * ks + j) > lim) x[j] = -INFINITY;
+                }
+#pragma unroll
+                for (int j = 0; j < TPM; ++j) e[j] = fast_exp2(x[j]);
+#pragma unroll
+                for (int j = 0; j < TPM; ++j) {
+                  if (j & 1) s1 += e[j]; else s0 += e[j];
+                }
+                PKV_CHUNK_END_SUMS(s0, s1);
+                if (ks == KS / 2 - 1) refill(ru, RFT, HALF);
+              }
+              z += s0 + s1;
+            };
+            if (dirty) fast(std::true_type{});
+            else fast(std::false_type{});
           }
           cur = nxt;
         };

@@ -1,0 +1,48 @@
+"""Seeded random shapes through both scoring paths, each compared with the oracle element by element."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2406_02069_amd import binding, synth
+from tests.parity import compare_layer
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _case(seed):
+    rs = np.random.RandomState(seed)
+    d = int(rs.choice([64, 128]))
+    Hkv = int(rs.choice([1, 2, 4, 8]))
+    G = int(rs.choice([1, 2, 4, 8]))
+    alpha = int(rs.choice([1, 3, 8, 16, 32, 64]))
+    if G * alpha > 512:                      # keep to shapes both paths accept
+        G = 512 // alpha
+    B = int(rs.choice([1, 2, 3]))
+    N = int(rs.randint(alpha + 2, 2600))
+    pool, pw = [(synth.POOL_NONE, 1), (synth.POOL_MAX, 3), (synth.POOL_MAX, 7), (synth.POOL_AVG, 5),
+                (synth.POOL_AVG, 9), (synth.POOL_MAX, 31)][rs.randint(6)]
+    k_l = int(rs.randint(alpha, min(N + 50, alpha + 400)))
+    lens = None
+    if rs.rand() < 0.5:
+        lens = rs.randint(0, N + 1, size=B).astype(np.int32)
+        lens[rs.randint(B)] = N              # at least one full-length sequence
+    return d, Hkv, G, alpha, B, N, pool, pw, k_l, lens
+
+
+@pytest.mark.parametrize("seed", range(60))
+@pytest.mark.parametrize("path", ["resident", "stream"])
+def test_random_shape(seed, path, monkeypatch):
+    monkeypatch.setenv("PKV_SCORE_PATH", path)
+    d, Hkv, G, alpha, B, N, pool, pw, k_l, lens = _case(seed)
+    print("case", seed, path, dict(d=d, Hkv=Hkv, G=G, alpha=alpha, B=B, N=N, pool=pool, pw=pw, k_l=k_l,
+                                   lens=None if lens is None else lens.tolist()), flush=True)
+    g = torch.Generator(device=DEV).manual_seed(5000 + seed)
+    scale = 1.0 + 2.0 * (seed % 3)           # wider logit ranges in some cases
+    Q = (torch.randn(B, Hkv * G, alpha, d, generator=g, device=DEV) * scale).to(torch.bfloat16)
+    K = torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    lens_dev = None if lens is None else torch.from_numpy(lens).to(DEV)
+    out = binding.compress_layer(Q, K, V, k_l, pool, pw, seq_lens=lens_dev, want_scores=True)
+    torch.cuda.synchronize()
+    compare_layer(Q, K, V, k_l, alpha, pool, pw, lens, out)

@@ -14,7 +14,10 @@
  * case, the harmonic closed form for identical keys (causal mask, window sum,
  * group mean), library 1-D pooling, brute-force sorting on tiny inputs,
  * planted one-hot / sink patterns, window retention, full-cache edge and the
- * closed forms of the budget sequence.  The integer rounding of the budgets,
+ * closed forms of the budget sequence; for the variant with supplied softmax
+ * denominators: a library log-sum-exp reproduces the plain softmax, the
+ * closed form exp(-ln c) = 1/c for all-zero logits, and the exp(-delta)
+ * scaling of a row whose denominator is shifted.  The integer rounding of the budgets,
  * the pool padding rule and the GQA mean are conventions the paper does not
  * fix ("parity unpinned" by the paper; pinned only to the stated reading).
  *
@@ -99,10 +102,18 @@ int pkvo_budgets(int32_t L, int32_t avg, int32_t beta, int32_t alpha,
  * Each window query at absolute position p attends causally to keys 0..p;
  * its softmax runs over exactly those p+1 keys (window keys included).
  * Scores are reported for prefix keys i < n-alpha only.
+ *
+ *   lse : [G][alpha] or NULL.  When given, lse[r] is taken as the natural
+ *         log of row r's softmax denominator, ln sum_{i<=p} exp(l_ri), as
+ *         the attention computation of prefill already produced it for the
+ *         instruction tokens (Sec. 4.2.2 reuses that attention); then
+ *         A_ri = exp(l_ri - lse[r]) and nothing is normalised here.  With
+ *         the exact value this is the same softmax.
  * ---------------------------------------------------------------------- */
 static void window_scores_unit(int32_t G, int32_t alpha, int32_t d, int32_t n,
                                const uint16_t *q, const uint16_t *k,
-                               double *s_head, double *s_mean) {
+                               const double *lse, double *s_head,
+                               double *s_mean) {
   const int32_t npre = n - alpha;
   const int32_t R = G * alpha;
   const double inv_sqrt_d = 1.0 / sqrt((double)d);
@@ -122,12 +133,16 @@ static void window_scores_unit(int32_t G, int32_t alpha, int32_t d, int32_t n,
       Ar[i] = dot * inv_sqrt_d;
       if (Ar[i] > mx) mx = Ar[i];
     }
-    double Z = 0.0;
-    for (int32_t i = 0; i <= p; ++i) {
-      Ar[i] = exp(Ar[i] - mx);
-      Z += Ar[i];
+    if (lse) {
+      for (int32_t i = 0; i <= p; ++i) Ar[i] = exp(Ar[i] - lse[r]);
+    } else {
+      double Z = 0.0;
+      for (int32_t i = 0; i <= p; ++i) {
+        Ar[i] = exp(Ar[i] - mx);
+        Z += Ar[i];
+      }
+      for (int32_t i = 0; i <= p; ++i) Ar[i] /= Z;
     }
-    for (int32_t i = 0; i <= p; ++i) Ar[i] /= Z;
     for (int32_t i = p + 1; i < n; ++i) Ar[i] = 0.0;
   }
   for (int32_t i = 0; i < npre; ++i) {
@@ -150,7 +165,18 @@ int pkvo_window_scores(int32_t G, int32_t alpha, int32_t d, int32_t n,
                        double *s_mean) {
   if (G < 1 || alpha < 1 || d < 1 || n <= alpha || !q || !k || !s_mean)
     return 1;
-  window_scores_unit(G, alpha, d, n, q, k, s_head, s_mean);
+  window_scores_unit(G, alpha, d, n, q, k, NULL, s_head, s_mean);
+  return 0;
+}
+
+/* The same with the softmax denominators supplied: lse [G][alpha], fp64. */
+int pkvo_window_scores_lse(int32_t G, int32_t alpha, int32_t d, int32_t n,
+                           const uint16_t *q, const uint16_t *k,
+                           const double *lse, double *s_head,
+                           double *s_mean) {
+  if (G < 1 || alpha < 1 || d < 1 || n <= alpha || !q || !k || !lse || !s_mean)
+    return 1;
+  window_scores_unit(G, alpha, d, n, q, k, lse, s_head, s_mean);
   return 0;
 }
 
@@ -245,13 +271,14 @@ int pkvo_topk(int32_t len, const double *p, int32_t kk, int32_t *idx) {
  *   window positions n-alpha..n-1.  7. copy the kept K and V rows.
  * Returns 0, or 1 for invalid arguments.
  * ---------------------------------------------------------------------- */
-int pkvo_compress_layer(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
-                        int32_t N, int32_t alpha, int32_t k_l, int32_t pool,
-                        int32_t pool_w, const uint16_t *Q_win,
-                        const uint16_t *K, const uint16_t *V,
-                        const int32_t *seq_lens, uint16_t *K_out,
-                        uint16_t *V_out, int32_t *idx_out, int32_t *count_out,
-                        double *pooled_out) {
+static int compress_layer_impl(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
+                               int32_t N, int32_t alpha, int32_t k_l,
+                               int32_t pool, int32_t pool_w,
+                               const uint16_t *Q_win, const uint16_t *K,
+                               const uint16_t *V, const int32_t *seq_lens,
+                               const float *lse, uint16_t *K_out,
+                               uint16_t *V_out, int32_t *idx_out,
+                               int32_t *count_out, double *pooled_out) {
   if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv || d < 1 || N < 1 || alpha < 1 ||
       k_l < alpha || pool_w < 1 || (pool_w % 2) == 0)
     return 1;
@@ -284,7 +311,14 @@ int pkvo_compress_layer(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
             Q_win + ((size_t)b * Hq + (size_t)g * G) * (size_t)alpha * d;
         double *s = (double *)malloc(sizeof(double) * (size_t)npre);
         double *p = (double *)malloc(sizeof(double) * (size_t)npre);
-        window_scores_unit(G, alpha, d, n, qg, Kg, NULL, s);
+        double *lg = NULL;
+        if (lse) { /* rows (b, g*G + h, t) of lse [B][Hq][alpha], fp32 */
+          lg = (double *)malloc(sizeof(double) * (size_t)G * alpha);
+          for (int32_t r = 0; r < G * alpha; ++r)
+            lg[r] = (double)lse[((size_t)b * Hq + (size_t)g * G) * alpha + r];
+        }
+        window_scores_unit(G, alpha, d, n, qg, Kg, lg, NULL, s);
+        free(lg);
         pkvo_pool(pool, pool_w, npre, s, p);
         pkvo_topk(npre, p, k_l - alpha, idx);
         for (int32_t t = 0; t < alpha; ++t) idx[k_l - alpha + t] = npre + t;
@@ -307,6 +341,36 @@ int pkvo_compress_layer(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
     }
   }
   return 0;
+}
+
+int pkvo_compress_layer(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
+                        int32_t N, int32_t alpha, int32_t k_l, int32_t pool,
+                        int32_t pool_w, const uint16_t *Q_win,
+                        const uint16_t *K, const uint16_t *V,
+                        const int32_t *seq_lens, uint16_t *K_out,
+                        uint16_t *V_out, int32_t *idx_out, int32_t *count_out,
+                        double *pooled_out) {
+  return compress_layer_impl(B, Hq, Hkv, d, N, alpha, k_l, pool, pool_w, Q_win,
+                             K, V, seq_lens, NULL, K_out, V_out, idx_out,
+                             count_out, pooled_out);
+}
+
+/* The same layer with caller-supplied softmax denominators:
+ *   lse : [B][Hq][alpha] fp32, lse[b][h][t] = ln sum_{i <= n_b-alpha+t}
+ *         exp(q_{h,t} . k_i / sqrt(d)) of sequence b (entries of sequences
+ *         that keep everything are not read). */
+int pkvo_compress_layer_lse(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
+                            int32_t N, int32_t alpha, int32_t k_l,
+                            int32_t pool, int32_t pool_w,
+                            const uint16_t *Q_win, const uint16_t *K,
+                            const uint16_t *V, const int32_t *seq_lens,
+                            const float *lse, uint16_t *K_out, uint16_t *V_out,
+                            int32_t *idx_out, int32_t *count_out,
+                            double *pooled_out) {
+  if (!lse) return 1;
+  return compress_layer_impl(B, Hq, Hkv, d, N, alpha, k_l, pool, pool_w, Q_win,
+                             K, V, seq_lens, lse, K_out, V_out, idx_out,
+                             count_out, pooled_out);
 }
 
 /* Number of OpenMP threads the scoring loop will use (for reports). */

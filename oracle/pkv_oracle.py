@@ -42,9 +42,12 @@ def _load():
         lib.pkvo_window_scores.argtypes = [i32, i32, i32, i32, p, p, p, p]
         lib.pkvo_pool.argtypes = [i32, i32, i32, p, p]
         lib.pkvo_topk.argtypes = [i32, p, i32, p]
+        lib.pkvo_window_scores_lse.argtypes = [i32, i32, i32, i32, p, p, p, p, p]
         lib.pkvo_compress_layer.argtypes = [i32] * 9 + [p] * 9
-        for f in (lib.pkvo_budgets, lib.pkvo_window_scores, lib.pkvo_pool, lib.pkvo_topk,
-                  lib.pkvo_compress_layer, lib.pkvo_num_threads):
+        lib.pkvo_compress_layer_lse.argtypes = [i32] * 9 + [p] * 10
+        for f in (lib.pkvo_budgets, lib.pkvo_window_scores, lib.pkvo_window_scores_lse, lib.pkvo_pool,
+                  lib.pkvo_topk, lib.pkvo_compress_layer, lib.pkvo_compress_layer_lse,
+                  lib.pkvo_num_threads):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -79,15 +82,23 @@ def budgets(L: int, avg_budget: int, beta: int, alpha: int) -> np.ndarray:
     return out[:L]
 
 
-def window_scores(q, k):
-    """q: [G, alpha, d] bf16, k: [n, d] bf16 -> (s_head [G, n-alpha], s_mean [n-alpha]) fp64."""
+def window_scores(q, k, lse=None):
+    """q: [G, alpha, d] bf16, k: [n, d] bf16 -> (s_head [G, n-alpha], s_mean [n-alpha]) fp64.
+
+    lse: optional [G, alpha] float64, the supplied natural-log softmax denominators."""
     qb, kb = _bits(q), _bits(k)
     G, alpha, d = qb.shape
     n = kb.shape[0]
     assert kb.shape[1] == d
     s_head = np.zeros((G, n - alpha), dtype=np.float64)
     s_mean = np.zeros(n - alpha, dtype=np.float64)
-    rc = _load().pkvo_window_scores(G, alpha, d, n, _ptr(qb), _ptr(kb), _ptr(s_head), _ptr(s_mean))
+    if lse is None:
+        rc = _load().pkvo_window_scores(G, alpha, d, n, _ptr(qb), _ptr(kb), _ptr(s_head), _ptr(s_mean))
+    else:
+        lb = np.ascontiguousarray(lse, dtype=np.float64)
+        assert lb.shape == (G, alpha)
+        rc = _load().pkvo_window_scores_lse(G, alpha, d, n, _ptr(qb), _ptr(kb), _ptr(lb), _ptr(s_head),
+                                            _ptr(s_mean))
     if rc != 0:
         raise ValueError("pkvo_window_scores: invalid arguments")
     return s_head, s_mean
@@ -112,8 +123,9 @@ def topk(p: np.ndarray, kk: int) -> np.ndarray:
 
 
 def compress_layer(Q_win, K, V, k_l: int, alpha: int, pool_kind: int, pool_w: int,
-                   seq_lens=None, want_pooled: bool = True):
+                   seq_lens=None, want_pooled: bool = True, lse=None):
     """One layer.  Q_win [B,Hq,alpha,d], K,V [B,Hkv,N,d] bf16 (torch) or uint16 bits (numpy).
+    lse: optional [B,Hq,alpha] float32 supplied natural-log softmax denominators.
 
     Returns dict(K_out, V_out (uint16 bits [B,Hkv,k_cap,d]), idx [B,Hkv,k_cap] int32,
     count [B] int32, pooled [B,Hkv,N] float64 or None)."""
@@ -132,9 +144,16 @@ def compress_layer(Q_win, K, V, k_l: int, alpha: int, pool_kind: int, pool_w: in
     idx = np.zeros((B, Hkv, k_cap), dtype=np.int32)
     count = np.zeros(B, dtype=np.int32)
     pooled = np.zeros((B, Hkv, N), dtype=np.float64) if want_pooled else None
-    rc = _load().pkvo_compress_layer(B, Hq, Hkv, d, N, alpha, k_l, pool_kind, pool_w,
-                                     _ptr(qb), _ptr(kb), _ptr(vb), _ptr(sl), _ptr(K_out), _ptr(V_out),
-                                     _ptr(idx), _ptr(count), _ptr(pooled))
+    if lse is None:
+        rc = _load().pkvo_compress_layer(B, Hq, Hkv, d, N, alpha, k_l, pool_kind, pool_w,
+                                         _ptr(qb), _ptr(kb), _ptr(vb), _ptr(sl), _ptr(K_out), _ptr(V_out),
+                                         _ptr(idx), _ptr(count), _ptr(pooled))
+    else:
+        lb = np.ascontiguousarray(lse, dtype=np.float32)
+        assert lb.shape == (B, Hq, alpha)
+        rc = _load().pkvo_compress_layer_lse(B, Hq, Hkv, d, N, alpha, k_l, pool_kind, pool_w,
+                                             _ptr(qb), _ptr(kb), _ptr(vb), _ptr(sl), _ptr(lb), _ptr(K_out),
+                                             _ptr(V_out), _ptr(idx), _ptr(count), _ptr(pooled))
     if rc != 0:
         raise ValueError("pkvo_compress_layer: invalid arguments")
     return dict(K_out=K_out, V_out=V_out, idx=idx, count=count, pooled=pooled)

@@ -146,3 +146,85 @@ def test_pool_closed_forms():
     assert list(np.nonzero(p)[0]) == list(range(9 - r, 9 + r + 1))
     with pytest.raises(ValueError):
         pkv_oracle.pool(pkv_oracle.POOL_MAX, 4, s)
+
+
+# ---- supplied softmax denominators (one-sweep variant of Sec. 4.2.2's window attention) ---------------
+
+
+def _library_lse(q, k, alpha):
+    """ln sum_{i <= p} exp(q.k_i / sqrt(d)) per window row with a library routine (scipy), fp64."""
+    from scipy.special import logsumexp
+
+    G, _, d = q.shape
+    n = k.shape[0]
+    logits = (q.double().reshape(G * alpha, d) @ k.double().T).numpy() / math.sqrt(d)
+    out = np.zeros(G * alpha)
+    for r in range(G * alpha):
+        p = n - alpha + r % alpha
+        out[r] = logsumexp(logits[r, : p + 1])
+    return out.reshape(G, alpha)
+
+
+def test_supplied_exact_denominators_reproduce_the_softmax():
+    torch.manual_seed(11)
+    for (G, alpha, n, d) in [(1, 1, 40, 64), (4, 8, 130, 128), (2, 5, 77, 64)]:
+        q = _bf16(torch.randn(G, alpha, d) * 2.0)
+        k = _bf16(torch.randn(n, d))
+        sh0, sm0 = pkv_oracle.window_scores(q, k)
+        sh1, sm1 = pkv_oracle.window_scores(q, k, lse=_library_lse(q, k, alpha))
+        np.testing.assert_allclose(sh1, sh0, rtol=1e-11)
+        np.testing.assert_allclose(sm1, sm0, rtol=1e-11)
+
+
+def test_supplied_denominator_single_visible_pair_closed_form():
+    # alpha = 1, all keys orthogonal to the query: every logit is 0; with lse = ln(c) every prefix
+    # key receives exactly 1/c whatever n is (nothing is renormalised).
+    d, n = 64, 20
+    q = torch.zeros(1, 1, d)
+    q[0, 0, 0] = 1.0
+    k = torch.zeros(n, d)
+    k[:, 1] = 3.0
+    for c in (2.0, 20.0, 0.5):
+        _, sm = pkv_oracle.window_scores(_bf16(q), _bf16(k), lse=np.array([[math.log(c)]]))
+        np.testing.assert_allclose(sm, np.full(n - 1, 1.0 / c), rtol=1e-14)
+
+
+def test_shifted_denominator_scales_each_rows_share():
+    # lse_r + delta_r multiplies row r's attention by exp(-delta_r): with one row per head and one
+    # head, the whole score vector scales; with several rows the per-head sums are the delta-weighted
+    # sums of the per-row softmaxes, which alpha = 1 heads expose one at a time.
+    torch.manual_seed(12)
+    G, n, d = 3, 90, 64
+    q = _bf16(torch.randn(G, 1, d))
+    k = _bf16(torch.randn(n, d))
+    base = _library_lse(q, k, 1)
+    sh0, _ = pkv_oracle.window_scores(q, k)
+    delta = np.array([[0.7], [-1.3], [0.0]])
+    sh1, sm1 = pkv_oracle.window_scores(q, k, lse=base + delta)
+    np.testing.assert_allclose(sh1, sh0 * np.exp(-delta), rtol=1e-11)
+    np.testing.assert_allclose(sm1, (sh0 * np.exp(-delta)).mean(axis=0), rtol=1e-11)
+
+
+def test_layer_with_supplied_denominators_indexes_them_by_batch_head_row():
+    # Full layer: every (b, head, t) row gets its own offset; only the matching layout of
+    # lse [B, Hq, alpha] reproduces the per-head scaled scores computed stage-wise above.
+    torch.manual_seed(13)
+    B, Hq, Hkv, alpha, N, d = 2, 4, 2, 3, 60, 64
+    G = Hq // Hkv
+    Q = _bf16(torch.randn(B, Hq, alpha, d))
+    K = _bf16(torch.randn(B, Hkv, N, d))
+    V = _bf16(torch.randn(B, Hkv, N, d))
+    rng = np.random.default_rng(5)
+    lse = np.zeros((B, Hq, alpha), dtype=np.float32)
+    for b in range(B):
+        for g in range(Hkv):
+            lse[b, g * G:(g + 1) * G] = _library_lse(Q[b, g * G:(g + 1) * G], K[b, g], alpha)
+    lse += rng.uniform(-0.5, 0.5, size=lse.shape).astype(np.float32)
+    out = pkv_oracle.compress_layer(Q, K, V, 16, alpha, pkv_oracle.POOL_NONE, 1, lse=lse)
+    for b in range(B):
+        for g in range(Hkv):
+            _, sm = pkv_oracle.window_scores(Q[b, g * G:(g + 1) * G], K[b, g],
+                                             lse=lse[b, g * G:(g + 1) * G].astype(np.float64))
+            np.testing.assert_allclose(out["pooled"][b, g, : N - alpha], sm, rtol=1e-14)
+            want = np.sort(np.argsort(-sm, kind="stable")[: 16 - alpha])
+            np.testing.assert_array_equal(out["idx"][b, g, : 16 - alpha], want)

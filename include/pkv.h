@@ -188,9 +188,40 @@ int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs,
                         size_t workspace_bytes, void* stream);
 
 /*
- * Measurement aid (no part of the method): pkv_compress_layers with the
- * caller's HIP events recorded around the kernels, so that a benchmark can
- * attribute device time to each kernel without a profiler.
+ * pkv_compress_layers with the softmax denominators of the window queries
+ * supplied by the caller.  The scores of Sec. 4.2.2 are taken from the
+ * attention of the instruction tokens, which prefill has already computed;
+ * an attention kernel that keeps its per-row log-sum-exp hands it over here,
+ * and the keys are then swept once instead of twice (no statistics sweep, no
+ * exchange between workgroups).
+ *
+ * lse        HOST array of L DEVICE pointers, each fp32 [B,Hq,alpha]
+ *            contiguous: lse[b][h][t] = ln sum_{i <= n_b-alpha+t}
+ *            exp(q_{b,h,t} . k_{b,g(h),i} / sqrt(d)), the natural log of the
+ *            denominator of window query t's causal softmax (Eq. Al), window
+ *            keys included.  The attention of step 2 becomes
+ *            exp(q.k/sqrt(d) - lse) and is not renormalised: results equal
+ *            pkv_compress_layers' to the accuracy of the supplied values.
+ *            Entries of sequences with n_b <= k_l are not read.  Non-finite
+ *            entries give meaningless (but in-range) selections.
+ * Everything else, and the errors, as pkv_compress_layers; a NULL lse or a
+ * NULL or misaligned lse[l] -> PKV_ERR_INVALID_ARG.  count_out is never -1
+ * here (nothing waits).
+ */
+int pkv_compress_layers_lse(int32_t L, const pkv_layer_desc* descs,
+                            const void* const* Q_win, const void* const* K,
+                            const void* const* V, const float* const* lse,
+                            const int32_t* seq_lens, void* const* K_out,
+                            void* const* V_out, int32_t* const* idx_out,
+                            int32_t* const* count_out,
+                            float* const* scores_out, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/*
+ * Measurement aid (no part of the method): pkv_compress_layers (lse NULL)
+ * or pkv_compress_layers_lse (lse given) with the caller's HIP events
+ * recorded around the kernels, so that a benchmark can attribute device time
+ * to each kernel without a profiler.
  *
  * events     HOST array of n_events hipEvent_t handles created by the caller
  *            with timing enabled.  events[0] is recorded on `stream` before
@@ -214,7 +245,8 @@ typedef enum {
 
 int pkv_compress_layers_profiled(
     int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
-    const void* const* K, const void* const* V, const int32_t* seq_lens,
+    const void* const* K, const void* const* V, const float* const* lse,
+    const int32_t* seq_lens,
     void* const* K_out, void* const* V_out, int32_t* const* idx_out,
     int32_t* const* count_out, float* const* scores_out, void* workspace,
     size_t workspace_bytes, void* stream, void* const* events,

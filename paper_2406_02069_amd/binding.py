@@ -20,7 +20,7 @@ POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers",
-           "pkv_compress_layers_profiled", "pkv_probe_read", "pkv_status_string"]
+           "pkv_compress_layers_lse", "pkv_compress_layers_profiled", "pkv_probe_read", "pkv_status_string"]
 
 
 class PkvError(RuntimeError):
@@ -55,6 +55,8 @@ def load() -> ctypes.CDLL:
         lib.pkv_compress_layer.restype = ctypes.c_int
         lib.pkv_compress_layers.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 10 + [ctypes.c_size_t, vp]
         lib.pkv_compress_layers.restype = ctypes.c_int
+        lib.pkv_compress_layers_lse.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 11 + [ctypes.c_size_t, vp]
+        lib.pkv_compress_layers_lse.restype = ctypes.c_int
         lib.pkv_status_string.argtypes = [ctypes.c_int]
         lib.pkv_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -153,7 +155,7 @@ class LayersCall:
 
     def __init__(self, Q_win: Sequence[torch.Tensor], K: Sequence[torch.Tensor], V: Sequence[torch.Tensor],
                  k_ls: Sequence[int], pool: int, pool_w: int, seq_lens: Optional[torch.Tensor] = None,
-                 want_scores: bool = False):
+                 want_scores: bool = False, lse: Optional[Sequence[torch.Tensor]] = None):
         L = len(K)
         assert len(Q_win) == L and len(V) == L and len(k_ls) == L
         self.L = L
@@ -171,18 +173,36 @@ class LayersCall:
                      [ptrs([o[i] for o in self.outputs]) for i in range(4)] + \
                      [ptrs([o[4] for o in self.outputs]) if want_scores else None]
         self.device = K[0].device
+        self._lse = None
+        if lse is not None:  # per layer: fp32 [B, Hq, alpha] contiguous, natural-log softmax denominators
+            B, Hq, alpha, _ = Q_win[0].shape
+            assert len(lse) == L
+            for t in lse:
+                assert t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == (B, Hq, alpha)
+            self.inputs = self.inputs + (list(lse),)
+            self._lse = ptrs(lse)
 
     def run(self):
-        rc = load().pkv_compress_layers(self.L, self.descs, *self._args, _p(self.workspace),
-                                        self.workspace.numel(), _stream_ptr(self.device))
+        tail = (_p(self.workspace), self.workspace.numel(), _stream_ptr(self.device))
+        if self._lse is not None:
+            a = self._args
+            rc = load().pkv_compress_layers_lse(self.L, self.descs, a[0], a[1], a[2], self._lse, *a[3:], *tail)
+        else:
+            rc = load().pkv_compress_layers(self.L, self.descs, *self._args, *tail)
         if rc != OK:
-            raise PkvError(rc, "pkv_compress_layers")
+            raise PkvError(rc, "pkv_compress_layers_lse" if self._lse is not None else "pkv_compress_layers")
         return self.outputs
 
 
 def compress_layers(Q_win, K, V, k_ls, pool, pool_w, seq_lens=None, want_scores=False):
     """pkv_compress_layers: all layers of one request batch.  Returns a list of per-layer output tuples."""
     return LayersCall(Q_win, K, V, k_ls, pool, pool_w, seq_lens, want_scores).run()
+
+
+def compress_layers_lse(Q_win, K, V, lse, k_ls, pool, pool_w, seq_lens=None, want_scores=False):
+    """pkv_compress_layers_lse: the same with the window queries' softmax denominators supplied per layer
+    (fp32 [B, Hq, alpha] each)."""
+    return LayersCall(Q_win, K, V, k_ls, pool, pool_w, seq_lens, want_scores, lse=lse).run()
 
 
 def probe_read(buf: torch.Tensor, sink: torch.Tensor) -> None:
@@ -234,13 +254,14 @@ def run_profiled(call: LayersCall, events: HipEvents):
     lib = load()
     if not hasattr(lib, "_prof_ready"):
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
-        lib.pkv_compress_layers_profiled.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 10 + \
+        lib.pkv_compress_layers_profiled.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 11 + \
             [ctypes.c_size_t, vp, vp, i32, vp, vp]
         lib.pkv_compress_layers_profiled.restype = ctypes.c_int
         lib._prof_ready = True
     ids = (ctypes.c_int32 * events.n)()
     used = ctypes.c_int32(0)
-    rc = lib.pkv_compress_layers_profiled(call.L, call.descs, *call._args, _p(call.workspace),
+    a = call._args
+    rc = lib.pkv_compress_layers_profiled(call.L, call.descs, a[0], a[1], a[2], call._lse, *a[3:], _p(call.workspace),
                                           call.workspace.numel(), _stream_ptr(call.device), events.handles,
                                           events.n, ids, ctypes.byref(used))
     if rc != OK:

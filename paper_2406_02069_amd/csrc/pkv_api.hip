@@ -95,6 +95,7 @@ struct LayerPtrs {
   int32_t* idx_out;
   int32_t* count_out;
   float* scores_out;
+  const float* lse;  // supplied softmax denominators, or null
 };
 
 static int check_ptrs(const LayerPtrs& p) {
@@ -103,6 +104,7 @@ static int check_ptrs(const LayerPtrs& p) {
     return PKV_ERR_INVALID_ARG;
   if (((uintptr_t)p.idx_out & 3) || ((uintptr_t)p.count_out & 3) || ((uintptr_t)p.scores_out & 3))
     return PKV_ERR_INVALID_ARG;
+  if ((uintptr_t)p.lse & 3) return PKV_ERR_INVALID_ARG;
   return PKV_OK;
 }
 
@@ -142,9 +144,9 @@ static bool device_fits_resident() {
 }
 
 // Start offset between consecutive workgroup groups, in 10 ns ticks (tuning hook: PKV_STAGGER).
-static int resident_stagger() {
+static int resident_stagger(int dflt) {
   if (const char* e = getenv("PKV_STAGGER")) return atoi(e);
-  return 250;
+  return dflt;
 }
 
 // Probes before a workgroup gives up waiting for its group (about 2 s; test hook: PKV_SPIN_LIMIT).
@@ -153,11 +155,13 @@ static int resident_spin_limit() {
   return 1 << 20;
 }
 
-static bool use_resident(const Plan& plan) {
+// lse_mode: with supplied denominators the workgroups of the persistent kernel never wait for each other, so it
+// runs on a device of any size.
+static bool use_resident(const Plan& plan, bool lse_mode) {
   if (const char* e = getenv("PKV_SCORE_PATH")) {  // test hook: "stream" forces the per-layer kernels
     if (!strcmp(e, "stream")) return false;
   }
-  return plan.resident_ok && device_fits_resident();
+  return plan.resident_ok && (lse_mode || device_fits_resident());
 }
 
 // Queue the kernels of L layers.  All arguments have been validated.
@@ -168,7 +172,8 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
   float* raw = reinterpret_cast<float*>(ws + plan.off_raw);
   float* pooled_ws = reinterpret_cast<float*>(ws + plan.off_pooled);
   const float kappa = (float)(1.4426950408889634 / sqrt((double)d.d));
-  const bool resident = use_resident(plan);
+  const bool lse_mode = ptrs[0].lse != nullptr;  // all layers or none (checked by the caller)
+  const bool resident = use_resident(plan, lse_mode);
   bool any_scores = false;
   for (int32_t l = 0; l < L; ++l) any_scores = any_scores || descs[l].k_l < d.N;
   if (rec) rec->begin(stream);
@@ -182,8 +187,10 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       for (int32_t i = 0; i < nl; ++i) {
         ra.layer[i].Q = static_cast<const uint16_t*>(ptrs[l0 + i].Q);
         ra.layer[i].K = static_cast<const uint16_t*>(ptrs[l0 + i].K);
+        ra.layer[i].lse = ptrs[l0 + i].lse;
         ra.layer[i].k_l = descs[l0 + i].k_l;
       }
+      ra.lse_mode = lse_mode ? 1 : 0;
       ra.seq_lens = seq_lens;
       ra.U = nl * plan.BH;
       ra.raw = raw + (size_t)l0 * plan.BH * d.N;
@@ -200,7 +207,7 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       ra.L = nl; ra.B = d.B; ra.Hq = d.Hq; ra.Hkv = d.Hkv; ra.G = plan.G; ra.alpha = d.alpha; ra.N = d.N;
       ra.R = plan.R; ra.Rpad = plan.res_Rpad; ra.nrb = plan.res_nrb; ra.TPU = plan.TPU;
       ra.ngroups = plan.ngroups; ra.UPG = plan.UPG;
-      ra.stagger = resident_stagger();
+      ra.stagger = resident_stagger(lse_mode ? 0 : 250);
       ra.spin_limit = resident_spin_limit();
       ra.d = d.d;
       ra.q_sb = d.q_sb; ra.q_sh = d.q_sh; ra.q_st = d.q_st;
@@ -228,8 +235,12 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       sa.q_sb = d.q_sb; sa.q_sh = d.q_sh; sa.q_st = d.q_st;
       sa.kv_sb = d.kv_sb; sa.kv_sh = d.kv_sh; sa.kv_st = d.kv_st;
       sa.kappa = kappa;
-      if (launch_score_stats(sa, stream) != hipSuccess) return PKV_ERR_HIP;
-      if (rec) rec->after(PKV_KERNEL_SCORE_STATS, stream);
+      sa.lse = ptrs[l].lse;
+      if (!lse_mode) {
+        if (launch_score_stats(sa, stream) != hipSuccess) return PKV_ERR_HIP;
+        if (rec) rec->after(PKV_KERNEL_SCORE_STATS, stream);
+      }
+      // (with supplied denominators this only converts them into the per-row normaliser table)
       if (launch_score_finalize(sa, stream) != hipSuccess) return PKV_ERR_HIP;
       if (rec) rec->after(PKV_KERNEL_SCORE_FINALIZE, stream);
       if (launch_score_accum(sa, stream) != hipSuccess) return PKV_ERR_HIP;
@@ -288,9 +299,11 @@ static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const vo
                                 const void* const* K, const void* const* V, const int32_t* seq_lens,
                                 void* const* K_out, void* const* V_out, int32_t* const* idx_out,
                                 int32_t* const* count_out, float* const* scores_out, void* workspace,
-                                size_t workspace_bytes, void* stream, Recorder* rec) {
+                                size_t workspace_bytes, void* stream, Recorder* rec,
+                                const float* const* lse = nullptr, bool want_lse = false) {
   if (L < 1 || L > kMaxLayers || !descs || !Q_win || !K || !V || !K_out || !V_out || !idx_out || !count_out)
     return PKV_ERR_INVALID_ARG;
+  if (want_lse && !lse) return PKV_ERR_INVALID_ARG;
   if ((uintptr_t)seq_lens & 3) return PKV_ERR_INVALID_ARG;
   LayerPtrs ptrs[kMaxLayers];
   for (int32_t l = 0; l < L; ++l) {
@@ -302,7 +315,8 @@ static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const vo
         a.kv_sb != b.kv_sb || a.kv_sh != b.kv_sh || a.kv_st != b.kv_st)
       return PKV_ERR_INVALID_ARG;
     ptrs[l] = {Q_win[l], K[l], V[l], K_out[l], V_out[l], idx_out[l], count_out[l],
-               scores_out ? scores_out[l] : nullptr};
+               scores_out ? scores_out[l] : nullptr, want_lse ? lse[l] : nullptr};
+    if (want_lse && !ptrs[l].lse) return PKV_ERR_INVALID_ARG;
     rc = check_ptrs(ptrs[l]);
     if (rc != PKV_OK) return rc;
   }
@@ -380,8 +394,18 @@ int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs, const void* cons
                               workspace, workspace_bytes, stream, nullptr);
 }
 
+int pkv_compress_layers_lse(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win, const void* const* K,
+                            const void* const* V, const float* const* lse, const int32_t* seq_lens,
+                            void* const* K_out, void* const* V_out, int32_t* const* idx_out,
+                            int32_t* const* count_out, float* const* scores_out, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  return compress_layers_impl(L, descs, Q_win, K, V, seq_lens, K_out, V_out, idx_out, count_out, scores_out,
+                              workspace, workspace_bytes, stream, nullptr, lse, true);
+}
+
 int pkv_compress_layers_profiled(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
-                                 const void* const* K, const void* const* V, const int32_t* seq_lens,
+                                 const void* const* K, const void* const* V, const float* const* lse,
+                                 const int32_t* seq_lens,
                                  void* const* K_out, void* const* V_out, int32_t* const* idx_out,
                                  int32_t* const* count_out, float* const* scores_out, void* workspace,
                                  size_t workspace_bytes, void* stream, void* const* events, int32_t n_events,
@@ -389,7 +413,7 @@ int pkv_compress_layers_profiled(int32_t L, const pkv_layer_desc* descs, const v
   if (!n_used) return PKV_ERR_INVALID_ARG;
   Recorder rec = {events, n_events, kernel_ids, 0};
   const int rc = compress_layers_impl(L, descs, Q_win, K, V, seq_lens, K_out, V_out, idx_out, count_out,
-                                      scores_out, workspace, workspace_bytes, stream, &rec);
+                                      scores_out, workspace, workspace_bytes, stream, &rec, lse, lse != nullptr);
   *n_used = rec.used;
   return rc;
 }

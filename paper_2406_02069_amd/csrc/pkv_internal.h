@@ -55,6 +55,7 @@ struct ScoreArgs {
   int32_t B, Hq, Hkv, G, alpha, N, k_l, R, Rpad, nrb, KC, nchunk, RT, d;
   int64_t q_sb, q_sh, q_st, kv_sb, kv_sh, kv_st;
   float kappa;   // log2(e) / sqrt(d)
+  const float* lse;  // [B][Hq][alpha] supplied natural-log softmax denominators, or null
 };
 
 
@@ -68,6 +69,7 @@ constexpr int kResidentMaxLayers = 96;  // per launch (kernel-argument table)
 struct ResidentLayer {
   const uint16_t* Q;
   const uint16_t* K;
+  const float* lse;  // [B][Hq][alpha] supplied natural-log softmax denominators, or null (two-sweep scoring)
   int32_t k_l;
   int32_t pad;
 };
@@ -87,6 +89,7 @@ struct ResidentArgs {
   int32_t ngroups;  // independent groups of workgroups: 512 / group size
   int32_t UPG;      // units a group works on at the same time: group size / TPU
   int32_t stagger;  // start offset between consecutive groups, in 10 ns ticks
+  int32_t lse_mode;    // 1: every layer carries lse; one sweep, no exchange between workgroups
   int32_t spin_limit;  // probes of a tagged word before a workgroup gives up waiting and raises the error word
   int64_t q_sb, q_sh, q_st, kv_sb, kv_sh, kv_st;
   float kappa, inv_kappa, inv_G;

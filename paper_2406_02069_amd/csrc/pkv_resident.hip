@@ -122,7 +122,9 @@ __device__ __forceinline__ u64 ld64(const u64* p) { return __hip_atomic_load(p, 
 // Accumulator element v of a lane (half h) belongs to tile row mrow(v, h) (32x32 MFMA output layout).
 __device__ __forceinline__ constexpr int mrow0(int v) { return 8 * (v >> 2) + (v & 3); }
 
-template <int D>
+// LSE: the per-row softmax denominators come from the caller (natural-log sums, one per window query); sweep 1
+// and the exchange between the workgroups are not needed then and every key is used once: a plain stream over K.
+template <int D, bool LSE>
 __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const ResidentArgs a) {
   constexpr int KS = D / 16;   // 32x32x16 MFMA k-steps per dot product
   constexpr int SEG = D / 8;   // 16-byte segments per row
@@ -138,7 +140,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   // per-row normalisers, ready for the matrix pipe: -c_r/kappa split into three bf16 (hi | mid << 16, lo)
   __shared__ u64 cfr[kResidentMaxRows];
   float2 (*stat)[2][kRowBlock] = reinterpret_cast<float2 (*)[2][kRowBlock]>(stat_mem);
-  int* qoff = reinterpret_cast<int*>(stat_mem);                                  // [kRowBlock]
+  // With supplied denominators there are no statistics: the memory holds a second normaliser table instead (the
+  // next unit's is filled while the current one is in use), and behind it the row-offset tables.
+  static_assert(sizeof(stat_mem) >= kResidentMaxRows * sizeof(u64) + 2 * kRowBlock * sizeof(int), "LDS reuse");
+  u64* cfr_alt = reinterpret_cast<u64*>(stat_mem);                                // [kResidentMaxRows], LSE only
+  int* qoff = reinterpret_cast<int*>(stat_mem) + (LSE ? 2 * kResidentMaxRows : 0);  // [kRowBlock]
+  int* qoff0 = qoff + kRowBlock;                                                  // [kRowBlock], LSE only: block 0, kept
   int* s_last_p = reinterpret_cast<int*>(stat_mem + kWaves * 2 * kRowBlock) - 1;  // last word
 #define s_last (*s_last_p)
 
@@ -201,6 +208,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     int u, n, npre, nparts;
     const uint16_t* Q;
     const uint16_t* K;
+    const float* lse;  // the unit's G * alpha denominators (row r = head * alpha + t), LSE only
   };
   // First unit at or after `u` (in steps of nslots) in which this workgroup has keys to score.
   auto find_unit = [&](int u, Unit& d) {
@@ -222,6 +230,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       d.nparts = (n + kResidentKeys - 1) / kResidentKeys;
       d.Q = a.layer[l].Q + (size_t)b * a.q_sb + (size_t)(g * a.G) * a.q_sh;
       d.K = a.layer[l].K + (size_t)b * a.kv_sb + (size_t)g * a.kv_sh;
+      if (LSE) d.lse = a.layer[l].lse + ((size_t)b * a.Hq + (size_t)g * a.G) * a.alpha;
       return;
     }
     d.u = a.U;
@@ -254,6 +263,45 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     u32x4* dst = qb + q_row0 * PITCH + q_seg;
 #pragma unroll
     for (int i = 0; i < QLD; ++i) dst[RPP * i * PITCH] = v[i];
+  };
+
+  // LSE: the staging of block 0 in two halves, so that its loads are in flight during a pass over the keys:
+  // request the rows into registers (row offsets from the kept table), write them to LDS later.
+  auto q_request = [&](const Unit& d, u32x4 (&v)[QLD]) {
+    const int tid_ = fresh(tid);
+    const int q_row0 = tid_ / SEG, q_seg = tid_ - q_row0 * SEG;
+    const char* src = reinterpret_cast<const char*>(d.Q) + q_seg * 16;
+#pragma unroll
+    for (int i = 0; i < QLD; ++i) {
+      const int off = qoff0[q_row0 + RPP * i];
+      v[i] = u32x4{0u, 0u, 0u, 0u};
+      if (off >= 0) v[i] = *reinterpret_cast<const u32x4*>(src + (uint32_t)off);
+    }
+  };
+  auto q_commit = [&](const u32x4 (&v)[QLD], u32x4* qb) {
+    const int tid_ = fresh(tid);
+    const int q_row0 = tid_ / SEG, q_seg = tid_ - q_row0 * SEG;
+    u32x4* dst = qb + q_row0 * PITCH + q_seg;
+#pragma unroll
+    for (int i = 0; i < QLD; ++i) dst[RPP * i * PITCH] = v[i];
+  };
+  // LSE: the unit's supplied denominators, likewise in two halves.  Table entry of row r: -c_r/kappa with
+  // c_r = lse_r * log2(e) (the logits are kept in the log2 domain); padding rows -inf.
+  constexpr int NL = kResidentMaxRows / kThreads;
+  auto lse_request = [&](const Unit& d, float (&lv)[NL]) {
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+      const int r = tid + kThreads * j;
+      lv[j] = INFINITY;
+      if (r < a.R) lv[j] = d.lse[r];
+    }
+  };
+  auto lse_commit = [&](const float (&lv)[NL], u64* table) {
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+      const int r = tid + kThreads * j;
+      if (r < a.Rpad) table[r] = split3(-(lv[j] * 1.44269504088896340736f) * a.inv_kappa);
+    }
   };
 
   // The wave's keys as MFMA operand fragments: kf[t][ks] = for key 32*t + (lane & 31), the 8 elements at
@@ -300,7 +348,20 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   if (cur_u.u >= a.U) return;
   int buf = 0;
   PKV_TN(0);
+  if (LSE && tid < kRowBlock) {  // row offsets of block 0: the same for every unit
+    int off = -1;
+    if (tid < a.R) {
+      const int hh = tid / a.alpha, t = tid - hh * a.alpha;
+      off = (int)(hh * a.q_sh + t * a.q_st) * 2;
+    }
+    qoff0[tid] = off;
+  }
   stage_q(cur_u, 0, qsmem);
+  if (LSE) {
+    float lv[NL];
+    lse_request(cur_u, lv);
+    lse_commit(lv, cfr);
+  }
   issue_k(cur_u, I0{}, I0{}, IKS{});
   issue_k(cur_u, I1{}, I0{}, IKS{});
   issue_k(cur_u, I2{}, I0{}, IKS{});
@@ -321,9 +382,14 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     const int lane_u = fresh(lane);
     const int l32 = lane_u & 31, hf = lane_u >> 5;
     const u32x4* q_lane = qb + l32 * PITCH + hf;
+    // normaliser table of this unit; LSE: the two tables alternate like the Q buffers
+    const u64* cfr_cur = (LSE && buf) ? cfr_alt : cfr;
+    u64* cfr_nxt = (LSE && !buf) ? cfr_alt : cfr;
+    bool q_staged = false;
     // LDS reads of one 32-row tile of Q as MFMA operand fragments
     auto q_frag = [&](int rt, int ks) { return as_frag(q_lane[32 * rt * PITCH + 2 * ks]); };
 
+    if constexpr (!LSE) {
     PKV_TN(1);
     // ---- sweep 1: per-row statistics over this workgroup's keys ----
     // Products: rows = keys (element v of a lane: key mrow0(v) + 4*hf of the tile), columns = query rows
@@ -513,7 +579,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     }
     __syncthreads();
     const bool last = s_last != 0;
-    bool q_staged = false;
     if (last) {
 #ifdef PKV_RES_TIMING
       tstamp[3] -= wall_clock64();
@@ -595,6 +660,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     }
     __builtin_amdgcn_s_setprio(0);
     PKV_T(2);
+    }  // !LSE
     PKV_TN(4);
 
     // ---- sweep 2: normalised probabilities summed over the query rows ----
@@ -605,7 +671,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     // written, and the next unit's keys are requested into the same registers.
     // Every load issued so far has long returned (sweep 1 consumed the keys).  Saying so here keeps the
     // compiler from waiting, in the second pass, for the next unit's keys requested after the first pass.
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    // (With supplied denominators there was no sweep 1: the second half of the keys may still be in flight, and
+    // should be.)
+    if constexpr (!LSE) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     float* raw = a.raw + (size_t)u * a.N;
     float e[kTiles];
 #pragma unroll
@@ -627,7 +695,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       // lane's query row in the first wave half (zeros in the second), operand B = (1, 1, 1, 0...).
       const u32x4 ones_u = (hf == 0) ? u32x4{0x3F803F80u, 0x00003F80u, 0u, 0u} : u32x4{0u, 0u, 0u, 0u};
       const bf16x8 ones = as_frag(ones_u);
-      const u64* cfr_lane = (hf == 0) ? cfr + rb * kRowBlock + l32 : reinterpret_cast<const u64*>(qsmem + SEG);  // second half: a zero word
+      const u64* cfr_lane = (hf == 0) ? cfr_cur + rb * kRowBlock + l32 : reinterpret_cast<const u64*>(qsmem + SEG);  // second half: a zero word
       const int cfr_step = (hf == 0) ? 32 : 0;
       bf16x8 bfr;
       auto load_bias = [&](int rt) {
@@ -703,7 +771,37 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
           issue_k(ru, F1, I0{}, IKS{});
         }
       };
+      // LSE: the next unit's Q block and denominators travel during the first pass and are put into the other
+      // LDS buffers after it (read from the start of the next unit, behind the barrier that ends this one)
+      u32x4 qv[QLD];
+      float lv[NL];
+      const bool prefetch = LSE && last_rb && has_next;
+#ifdef PKV_RES_TIMING
+      if constexpr (LSE) {  // time spent waiting for the first half of the keys (the second half stays in flight)
+        PKV_TN(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * KS) & 15) | (((2 * KS) >> 4) << 14));
+        PKV_T(0);
+        PKV_TN(1);
+      }
+#endif
+      if (prefetch) {
+        lse_request(nxt_u, lv);
+        if (a.nrb == 1) q_request(nxt_u, qv);
+      }
       pass(I0{}, I1{}, std::false_type{}, I2{}, I3{}, cur_u);
+#ifdef PKV_RES_TIMING
+      if constexpr (LSE) {
+        PKV_T(1);
+        PKV_TN(2);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        PKV_T(2);
+        PKV_TN(3);
+      }
+#endif
+      if (prefetch) {
+        lse_commit(lv, cfr_nxt);
+        if (a.nrb == 1) q_commit(qv, qsmem + (buf ^ 1) * QBUF);
+      }
       // key tiles 0,1 are done: the next unit's are requested into the same registers during the second pass
       // (after the last unit the current ones are fetched once more: harmless, and the code stays branch-free)
       pass(I2{}, I3{}, LAST, I0{}, I1{}, has_next ? nxt_u : cur_u);
@@ -712,10 +810,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         issue_k(has_next ? nxt_u : cur_u, I2{}, I0{}, IKS{});
         issue_k(has_next ? nxt_u : cur_u, I3{}, I0{}, IKS{});
       }
+#ifdef PKV_RES_TIMING
+      if constexpr (LSE) PKV_T(3);
+#endif
     };
     for (int rb = 0; rb + 1 < a.nrb; ++rb) s2_block(rb, std::false_type{});
     s2_block(a.nrb - 1, std::true_type{});
-    if (has_next && !q_staged) stage_q(nxt_u, 0, qsmem + (buf ^ 1) * QBUF);
+    if (!LSE && has_next && !q_staged) stage_q(nxt_u, 0, qsmem + (buf ^ 1) * QBUF);
     lds_barrier();  // cfr / stat and the Q buffers change hands
     PKV_T(4);
     cur_u = nxt_u;
@@ -736,29 +837,35 @@ __global__ void zero_kernel(int32_t* p, int n) {
 
 }  // namespace
 
-template <int D>
+template <int D, bool LSE>
 static hipError_t launch_resident(const ResidentArgs& a, hipStream_t s) {
   constexpr int SEG = D / 8;
   const size_t dyn = (size_t)2 * kRowBlock * lds_pitch<SEG>() * sizeof(u32x4);  // two Q buffers
   static bool attr_set = false;
   if (!attr_set) {  // raise the dynamic LDS limit once (idempotent; no allocation)
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_resident_kernel<D>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_resident_kernel<D, LSE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(score_resident_kernel<D>, dim3(kResidentGrid), dim3(kThreads), dyn, s, a);
+  hipLaunchKernelGGL((score_resident_kernel<D, LSE>), dim3(kResidentGrid), dim3(kThreads), dyn, s, a);
   return hipGetLastError();
 }
 
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s) {
-  // the counters, the error word and the tagged normaliser words must start at zero
+  // the counters, the error word and the tagged normaliser words must start at zero (with supplied denominators
+  // only the error word is looked at, by the selection kernel)
   const int nz = a.sync_words;
   hipLaunchKernelGGL(zero_kernel, dim3((nz + 255) / 256), dim3(256), 0, s, a.zero_base, nz);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (a.d == 128) return launch_resident<128>(a, s);
-  if (a.d == 64) return launch_resident<64>(a, s);
+  if (a.lse_mode) {
+    if (a.d == 128) return launch_resident<128, true>(a, s);
+    if (a.d == 64) return launch_resident<64, true>(a, s);
+  } else {
+    if (a.d == 128) return launch_resident<128, false>(a, s);
+    if (a.d == 64) return launch_resident<64, false>(a, s);
+  }
   return hipErrorInvalidValue;
 }
 

@@ -254,7 +254,11 @@ __global__ __launch_bounds__(256) void finalize_kernel(const ScoreArgs a) {
   if (a.k_l >= n) return;
   for (int r = threadIdx.x; r < a.Rpad; r += blockDim.x) {
     float c = INFINITY;  // padding rows contribute exp2(-inf) = 0
-    if (r < a.R) {
+    if (r < a.R && a.lse) {
+      // supplied natural-log denominator of row r = head * alpha + t of this group, into the log2 domain
+      const int g = bg - b * a.Hkv;
+      c = a.lse[((size_t)b * a.Hq + (size_t)g * a.G) * a.alpha + r] * 1.44269504088896340736f;
+    } else if (r < a.R) {
       const float2* p = a.part + ((size_t)bg * a.Rpad + r) * a.nchunk;
       float m = -INFINITY, z = 0.f;
       for (int ch = 0; ch < a.nchunk; ++ch) merge_stats(m, z, p[ch].x, p[ch].y);

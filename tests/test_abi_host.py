@@ -129,3 +129,19 @@ def test_probe_read_rejects_bad_arguments_before_any_launch():
     assert lib.pkv_probe_read(0x1000, 0, 0x2000, None) == binding.ERR_INVALID_ARG       # empty
     assert lib.pkv_probe_read(0x1000, 1000, 0x2000, None) == binding.ERR_INVALID_ARG    # not a multiple of 16
     assert lib.pkv_probe_read(0x1008, 1024, 0x2000, None) == binding.ERR_INVALID_ARG    # misaligned buffer
+
+
+def test_compress_layers_lse_rejects_missing_or_misaligned_denominators():
+    lib = binding.load()
+    descs = (binding.LayerDesc * 2)(_desc(), _desc())
+    arr = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    I = binding.ERR_INVALID_ARG
+
+    def call(lse, ws_bytes=1 << 30):
+        return lib.pkv_compress_layers_lse(2, descs, arr, arr, arr, lse, None, arr, arr, arr, arr, None,
+                                           0x10000, ws_bytes, None)
+
+    assert call(None) == I                                         # no table of denominators
+    assert call((ctypes.c_void_p * 2)(0x1000, None)) == I          # a layer without them
+    assert call((ctypes.c_void_p * 2)(0x1000, 0x2002)) == I        # not 4-byte aligned
+    assert call(arr, ws_bytes=16) == binding.ERR_WORKSPACE         # valid so far: fails at the workspace check

@@ -1,0 +1,158 @@
+"""One-sweep scoring with caller-supplied softmax denominators (pkv_compress_layers_lse) vs. the CPU oracle's
+variant that takes the same denominators, element by element, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pkv_oracle
+from paper_2406_02069_amd import binding, prefill_stub, synth
+from tests.parity import compare_layer
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(params=["resident", "stream"])
+def score_path(request, monkeypatch):
+    monkeypatch.setenv("PKV_SCORE_PATH", request.param)
+    return request.param
+
+
+def _lens_dev(lens):
+    return None if lens is None else torch.from_numpy(np.asarray(lens, dtype=np.int32)).to(DEV)
+
+
+def _rand(B, Hq, Hkv, d, N, alpha, seed, scale=1.0):
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    Q = (torch.randn(B, Hq, alpha, d, generator=g, device=DEV) * scale).to(torch.bfloat16)
+    K = torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    return Q, K, V
+
+
+def _check(Q, K, V, lse, k_l, alpha, pool, pw, lens=None, ref_without_lse=False):
+    """One layer through the LSE entry point against the oracle given the same fp32 denominators (or, with
+    ref_without_lse, against the oracle's own softmax: the supplied values are then the exact ones)."""
+    out = binding.compress_layers_lse([Q], [K], [V], [lse], [k_l], pool, pw, seq_lens=_lens_dev(lens),
+                                      want_scores=True)[0]
+    torch.cuda.synchronize()
+    lse_np = None if ref_without_lse else np.nan_to_num(lse.cpu().numpy(), nan=0.0)
+    ref = pkv_oracle.compress_layer(Q, K, V, k_l, alpha, pool, pw, seq_lens=lens, lse=lse_np)
+    return compare_layer(Q, K, V, k_l, alpha, pool, pw, lens, out, ref=ref), out
+
+
+def test_config0_all_layers(score_path):
+    w = synth.WORKLOADS[0]
+    ks = binding.budgets(w.L, w.avg_budgets[0], w.beta, w.alpha)
+    for layer in range(w.L):
+        print("lse config0 layer", layer, flush=True)
+        Q, K, V, lens = synth.make_layer(w, layer, DEV)
+        lse = prefill_stub.window_lse(Q, K, lens)
+        _check(Q, K, V, lse, ks[layer], w.alpha, w.pool, w.pool_w, lens)
+
+
+@pytest.mark.parametrize("cfg,N", [(1, 1500), (1, 4099), (2, 2500), (4, 1111)])
+def test_scaled_configs_ragged_tiles(cfg, N, score_path):
+    w = synth.WORKLOADS[cfg].scaled(N=N, L=2)
+    ks = binding.budgets(w.L, w.avg_budgets[0], w.beta, w.alpha)
+    for layer in range(w.L):
+        print("lse scaled config", cfg, "N", N, "layer", layer, flush=True)
+        Q, K, V, lens = synth.make_layer(w, layer, DEV)
+        lse = prefill_stub.window_lse(Q, K, lens)
+        _check(Q, K, V, lse, ks[layer], w.alpha, w.pool, w.pool_w, lens)
+
+
+def test_ragged_batch_unread_rows_may_hold_anything(score_path):
+    # sequences that keep everything (n_b <= k_l, including n_b < alpha and n_b = 0) never read their rows
+    alpha = 8
+    Q, K, V = _rand(4, 8, 2, 128, 900, alpha, seed=21)
+    lens = np.array([900, 40, 3, 0], dtype=np.int32)
+    lse = prefill_stub.window_lse(Q, K, lens)
+    lse[1:] = float("nan")
+    for k_l in (40, 64):
+        print("lse ragged k_l", k_l, flush=True)
+        st, out = _check(Q, K, V, lse, k_l, alpha, synth.POOL_MAX, 7, lens)
+        assert not torch.isnan(out[4][0, :, : 900 - alpha]).any()
+
+
+@pytest.mark.parametrize("d,Hq,Hkv,alpha", [(64, 8, 8, 8), (64, 16, 2, 8), (64, 12, 4, 5), (128, 4, 4, 1),
+                                             (128, 28, 4, 16), (128, 64, 8, 64), (64, 6, 2, 37)])
+def test_head_geometries(d, Hq, Hkv, alpha, score_path):
+    Q, K, V = _rand(2, Hq, Hkv, d, 1234, alpha, seed=d + Hq + alpha)
+    lse = prefill_stub.window_lse(Q, K)
+    for pool, pw in ((synth.POOL_MAX, 7), (synth.POOL_NONE, 1)):
+        print("lse geometry", d, Hq, Hkv, alpha, pool, pw, flush=True)
+        _check(Q, K, V, lse, alpha + 100, alpha, pool, pw)
+
+
+def test_supplied_values_are_used_row_by_row(score_path):
+    # every (sequence, head, window row) gets its own offset: the scores must follow the supplied values,
+    # indexed [b][h][t], not the true denominators
+    alpha = 5
+    Q, K, V = _rand(2, 12, 4, 64, 700, alpha, seed=33)
+    lse = prefill_stub.window_lse(Q, K)
+    g = torch.Generator(device=DEV).manual_seed(34)
+    lse = lse + (torch.rand(lse.shape, generator=g, device=DEV) * 4.0 - 2.0)
+    st, out = _check(Q, K, V, lse, 60, alpha, synth.POOL_NONE, 1)
+    # ... and differ from the standard scores (the offsets are not a no-op)
+    std = binding.compress_layer(Q, K, V, 60, synth.POOL_NONE, 1, want_scores=True)
+    torch.cuda.synchronize()
+    assert not torch.allclose(out[4][:, :, : 700 - alpha], std[4][:, :, : 700 - alpha], rtol=1e-2, atol=0)
+
+
+def test_exact_denominators_reproduce_the_two_sweep_result(score_path):
+    # supplied = exact (fp64 log-sum-exp rounded to fp32): same scores and kept sets as the plain definition
+    # (the oracle WITHOUT supplied values), which pins the convention: natural log, causal range, window included
+    for (B, Hq, Hkv, d, N, alpha, scale) in [(1, 8, 2, 128, 3000, 8, 1.0), (2, 4, 4, 64, 1100, 16, 3.0)]:
+        print("lse exact", B, Hq, Hkv, d, N, alpha, flush=True)
+        Q, K, V = _rand(B, Hq, Hkv, d, N, alpha, seed=N, scale=scale)
+        lse = prefill_stub.window_lse(Q, K)
+        _check(Q, K, V, lse, 128, alpha, synth.POOL_MAX, 7, ref_without_lse=True)
+
+
+def test_many_layers_in_one_call(score_path):
+    # more layers than one launch of the persistent kernel holds (96), each with its own denominators
+    L, alpha = 100, 4
+    Q, K, V = _rand(1, 4, 2, 64, 600, alpha, seed=77)
+    Qs = [Q.roll(l, dims=2).contiguous() for l in range(L)]
+    Ks = [K.roll(3 * l, dims=2).contiguous() for l in range(L)]
+    lses = [prefill_stub.window_lse(Qs[l], Ks[l]) for l in range(L)]
+    ks = [alpha + 1 + (7 * l) % 90 for l in range(L)]
+    outs = binding.compress_layers_lse(Qs, Ks, [V] * L, lses, ks, synth.POOL_AVG, 5, want_scores=True)
+    torch.cuda.synchronize()
+    for l in (0, 1, 50, 95, 96, 99):
+        print("lse many layers: layer", l, flush=True)
+        ref = pkv_oracle.compress_layer(Qs[l], Ks[l], V, ks[l], alpha, synth.POOL_AVG, 5, lse=lses[l].cpu().numpy())
+        compare_layer(Qs[l], Ks[l], V, ks[l], alpha, synth.POOL_AVG, 5, None, outs[l], ref=ref)
+
+
+def _case(seed):
+    rs = np.random.RandomState(1000 + seed)
+    d = int(rs.choice([64, 128]))
+    Hkv = int(rs.choice([1, 2, 4, 8]))
+    G = int(rs.choice([1, 2, 4, 8]))
+    alpha = int(rs.choice([1, 3, 8, 16, 32, 64]))
+    if G * alpha > 512:
+        G = 512 // alpha
+    B = int(rs.choice([1, 2, 3]))
+    N = int(rs.randint(alpha + 2, 2600))
+    pool, pw = [(synth.POOL_NONE, 1), (synth.POOL_MAX, 3), (synth.POOL_MAX, 7), (synth.POOL_AVG, 5),
+                (synth.POOL_AVG, 9), (synth.POOL_MAX, 31)][rs.randint(6)]
+    k_l = int(rs.randint(alpha, min(N + 50, alpha + 400)))
+    lens = None
+    if rs.rand() < 0.5:
+        lens = rs.randint(0, N + 1, size=B).astype(np.int32)
+        lens[rs.randint(B)] = N
+    return d, Hkv, G, alpha, B, N, pool, pw, k_l, lens
+
+
+@pytest.mark.parametrize("seed", range(30))
+@pytest.mark.parametrize("path", ["resident", "stream"])
+def test_random_shape(seed, path, monkeypatch):
+    monkeypatch.setenv("PKV_SCORE_PATH", path)
+    d, Hkv, G, alpha, B, N, pool, pw, k_l, lens = _case(seed)
+    print("lse case", seed, path, dict(d=d, Hkv=Hkv, G=G, alpha=alpha, B=B, N=N, pool=pool, pw=pw, k_l=k_l,
+                                       lens=None if lens is None else lens.tolist()), flush=True)
+    Q, K, V = _rand(B, Hkv * G, Hkv, d, N, alpha, seed=7000 + seed, scale=1.0 + 2.0 * (seed % 3))
+    lse = prefill_stub.window_lse(Q, K, lens)
+    _check(Q, K, V, lse, k_l, alpha, pool, pw, lens)

@@ -171,7 +171,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   }
   const int sub = slot / a.TPU;
   const int part_id = slot - sub * a.TPU;
-  if (sub >= a.UPG) return;  // no work for this workgroup at this shape
+  if (!LSE && sub >= a.UPG) return;  // no work for this workgroup at this shape
   const int slot_id = group * a.UPG + sub;  // one of nslots concurrent units
   const int nslots = a.ngroups * a.UPG;
   float2* part_base = a.part + (size_t)slot_id * a.TPU * a.Rpad;
@@ -209,6 +209,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     const uint16_t* Q;
     const uint16_t* K;
     const float* lse;  // the unit's G * alpha denominators (row r = head * alpha + t), LSE only
+    int wkey0;         // first key of this wave in the unit, LSE only (there the part changes from unit to unit)
   };
   // First unit at or after `u` (in steps of nslots) in which this workgroup has keys to score.
   auto find_unit = [&](int u, Unit& d) {
@@ -234,6 +235,47 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       return;
     }
     d.u = a.U;
+  };
+  // LSE: nothing ties a workgroup to a group or a part, so the (unit, part) items are handed out on demand: item
+  // j = unit j / TPU, part j % TPU.  Every workgroup starts with the items blockIdx and 512 + blockIdx and draws
+  // further ones from a counter; a workgroup slowed down by its neighbours or its memory channels just takes
+  // fewer.  An item without work (sequence kept whole, part beyond its end) is skipped.
+  const int n_items = a.U * a.TPU;
+  // four words: [0], [1] for the draws made ahead (used alternately), [2] for replacement draws, [3] spare
+  int* s_item = reinterpret_cast<int*>(stat_mem + kWaves * 2 * kRowBlock) - 4;
+  auto decode = [&](int item, Unit& d) -> bool {
+    const int u = item / a.TPU, part = item - u * a.TPU;
+    const int l = u / BH;
+    const int bg = u - l * BH;
+    const int b = bg / a.Hkv;
+    const int g = bg - b * a.Hkv;
+    int n = a.N;
+    if (a.seq_lens) {
+      n = a.seq_lens[b];
+      n = n < 0 ? 0 : (n > a.N ? a.N : n);
+    }
+    if (a.layer[l].k_l >= n || part * kResidentKeys >= n) return false;
+    d.u = u;
+    d.n = n;
+    d.npre = n - a.alpha;
+    d.nparts = 0;
+    d.Q = a.layer[l].Q + (size_t)b * a.q_sb + (size_t)(g * a.G) * a.q_sh;
+    d.K = a.layer[l].K + (size_t)b * a.kv_sb + (size_t)g * a.kv_sh;
+    d.lse = a.layer[l].lse + ((size_t)b * a.Hq + (size_t)g * a.G) * a.alpha;
+    d.wkey0 = part * kResidentKeys + wave * (kTiles * 32);
+    return true;
+  };
+  // The item `it`, or the next one with work, as unit d (d.u = U when the items have run out).  Called by all
+  // threads together; drawing a replacement involves the whole workgroup (rare).
+  auto take = [&](int it, Unit& d) {
+    while (it < n_items && !decode(it, d)) {
+      __syncthreads();  // everyone holds the same `it` and is done with the previous replacement
+      if (tid == 0)
+        s_item[2] = 2 * kResidentGrid + __hip_atomic_fetch_add(&a.cnt[0], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __syncthreads();
+      it = s_item[2];
+    }
+    if (it >= n_items) d.u = a.U;
   };
 
   // Stage a 128-row block of Q in LDS.  qoff[row] = byte offset of the row (-1: padding row).
@@ -265,28 +307,30 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     for (int i = 0; i < QLD; ++i) dst[RPP * i * PITCH] = v[i];
   };
 
-  // LSE: the staging of block 0 in two halves, so that its loads are in flight during a pass over the keys:
-  // request the rows into registers (row offsets from the kept table), write them to LDS later.
-  auto q_request = [&](const Unit& d, u32x4 (&v)[QLD]) {
+  // LSE: block 0 of a unit's Q goes to LDS in two halves (H = 0, 1: every second group of rows), each requested
+  // into registers at one point and written to LDS at a later one, so that the loads travel in the shadow of a
+  // pass while only a few registers wait for them.  Row offsets come from the kept table; no barrier here.
+  constexpr int QH = QLD / 2;
+  auto q_request = [&](const Unit& d, auto H, u32x4 (&v)[QH]) {
     const int tid_ = fresh(tid);
     const int q_row0 = tid_ / SEG, q_seg = tid_ - q_row0 * SEG;
     const char* src = reinterpret_cast<const char*>(d.Q) + q_seg * 16;
 #pragma unroll
-    for (int i = 0; i < QLD; ++i) {
-      const int off = qoff0[q_row0 + RPP * i];
+    for (int i = 0; i < QH; ++i) {
+      const int off = qoff0[q_row0 + RPP * (2 * i + decltype(H)::value)];
       v[i] = u32x4{0u, 0u, 0u, 0u};
       if (off >= 0) v[i] = *reinterpret_cast<const u32x4*>(src + (uint32_t)off);
     }
   };
-  auto q_commit = [&](const u32x4 (&v)[QLD], u32x4* qb) {
+  auto q_commit = [&](const u32x4 (&v)[QH], auto H, u32x4* qb) {
     const int tid_ = fresh(tid);
     const int q_row0 = tid_ / SEG, q_seg = tid_ - q_row0 * SEG;
     u32x4* dst = qb + q_row0 * PITCH + q_seg;
 #pragma unroll
-    for (int i = 0; i < QLD; ++i) dst[RPP * i * PITCH] = v[i];
+    for (int i = 0; i < QH; ++i) dst[RPP * (2 * i + decltype(H)::value) * PITCH] = v[i];
   };
-  // LSE: the unit's supplied denominators, likewise in two halves.  Table entry of row r: -c_r/kappa with
-  // c_r = lse_r * log2(e) (the logits are kept in the log2 domain); padding rows -inf.
+  // LSE: the unit's supplied denominators.  Table entry of row r: -c_r/kappa with c_r = lse_r * log2(e) (the logits
+  // are kept in the log2 domain); padding rows -inf.
   constexpr int NL = kResidentMaxRows / kThreads;
   auto lse_request = [&](const Unit& d, float (&lv)[NL]) {
 #pragma unroll
@@ -313,7 +357,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     constexpr int t = decltype(T)::value;
     const int lane_ = fresh(lane);
     const int l32 = lane_ & 31, hf = lane_ >> 5;
-    const int key = min(wkey0 + 32 * t + l32, d.n - 1);
+    const int key = min((LSE ? d.wkey0 : wkey0) + 32 * t + l32, d.n - 1);
     // 32-bit byte offsets from the head's first key (the host admits only shapes where they fit)
     const char* rowp = reinterpret_cast<const char*>(d.K) + 16 * hf + (uint32_t)key * ((uint32_t)a.kv_st * 2u);
 #pragma unroll
@@ -344,7 +388,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
 
   if (tid == 0) qsmem[SEG] = u32x4{0u, 0u, 0u, 0u};  // pad slot of row 0: never written by the staging
   Unit cur_u, nxt_u;
-  find_unit(slot_id, cur_u);
+  int drawn = 0;  // LSE: the counter's value at this unit's draw (the item is 1024 + that)
+  if constexpr (LSE) {
+    take((int)blockIdx.x, cur_u);
+    if (cur_u.u < a.U) take(kResidentGrid + (int)blockIdx.x, nxt_u);
+  } else {
+    find_unit(slot_id, cur_u);
+  }
   if (cur_u.u >= a.U) return;
   int buf = 0;
   PKV_TN(0);
@@ -364,6 +414,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   }
   issue_k(cur_u, I0{}, I0{}, IKS{});
   issue_k(cur_u, I1{}, I0{}, IKS{});
+  // LSE: the unit loop is entered as it comes round: first half of the keys arrived, second half in flight.  (Else
+  // the first pass, which sees both ways in, would wait for part of the second half in every unit.)
+  if constexpr (LSE) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   issue_k(cur_u, I2{}, I0{}, IKS{});
   issue_k(cur_u, I3{}, I0{}, IKS{});
   __syncthreads();
@@ -371,9 +424,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
 
   while (cur_u.u < a.U) {
     const int u = cur_u.u, n = cur_u.n, npre = cur_u.npre, nparts = cur_u.nparts;
-    find_unit(u + nslots, nxt_u);
+    if constexpr (!LSE) find_unit(u + nslots, nxt_u);
     const bool has_next = nxt_u.u < a.U;
-    const bool has_keys = wkey0 < n;                      // wave-uniform
+    const int wkey = LSE ? cur_u.wkey0 : wkey0;
+    const bool has_keys = wkey < n;                       // wave-uniform
     // tile t needs masks iff it reaches beyond the prefix (causal window, end of the sequence)
     int dirty_mask = 0;
 #pragma unroll
@@ -762,7 +816,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
             for (int t = ta; t <= tb; ++t) {
               float tot = e[t];
               tot += __shfl_xor(tot, 32);
-              const int key = wkey0 + 32 * t + l32;
+              const int key = wkey + 32 * t + l32;
               if (hf == 0 && key < npre) raw[key] = tot * a.inv_G;
             }
           }
@@ -771,11 +825,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
           issue_k(ru, F1, I0{}, IKS{});
         }
       };
-      // LSE: the next unit's Q block and denominators travel during the first pass and are put into the other
-      // LDS buffers after it (read from the start of the next unit, behind the barrier that ends this one)
-      u32x4 qv[QLD];
-      float lv[NL];
-      const bool prefetch = LSE && last_rb && has_next;
 #ifdef PKV_RES_TIMING
       if constexpr (LSE) {  // time spent waiting for the first half of the keys (the second half stays in flight)
         PKV_TN(0);
@@ -784,10 +833,16 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         PKV_TN(1);
       }
 #endif
-      if (prefetch) {
-        lse_request(nxt_u, lv);
-        if (a.nrb == 1) q_request(nxt_u, qv);
-      }
+      // LSE: the next unit's denominators and Q block travel while this unit is computed: the denominators and one
+      // half of the rows during the first pass, the other half during the second.  Each is written to the other
+      // LDS buffers (read from the start of the next unit, behind the barrier that ends this one) at a place where
+      // the wave waits for nothing younger than what it needs there anyway.
+      u32x4 qv[QH];
+      float lv[NL];
+      const bool prefetch = LSE && last_rb && has_next;
+      const bool prefetch_q = prefetch && a.nrb == 1;
+      if (prefetch) lse_request(nxt_u, lv);
+      if (prefetch_q) q_request(nxt_u, I0{}, qv);
       pass(I0{}, I1{}, std::false_type{}, I2{}, I3{}, cur_u);
 #ifdef PKV_RES_TIMING
       if constexpr (LSE) {
@@ -798,14 +853,21 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         PKV_TN(3);
       }
 #endif
-      if (prefetch) {
-        lse_commit(lv, cfr_nxt);
-        if (a.nrb == 1) q_commit(qv, qsmem + (buf ^ 1) * QBUF);
-      }
+      if (prefetch) lse_commit(lv, cfr_nxt);
+      if (prefetch_q) q_commit(qv, I0{}, qsmem + (buf ^ 1) * QBUF);
+      // The item after the next one is drawn here: every earlier request of the wave has just been waited for and
+      // every later one is younger, so that no wait for keys can mistake it for one of them, and the answer is
+      // back long before the unit ends.  Two lanes draw, the second one adding nothing to the spare word beside
+      // the error word (err + 2 is the first counter word): what a single lane asks for is moved to a scalar
+      // register at once, and the wave would wait for the answer on the spot.
+      if (LSE && last_rb && tid < 2)
+        drawn = __hip_atomic_fetch_add(a.err + 2 - fresh(tid), 1 - fresh(tid), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (prefetch_q) q_request(nxt_u, I1{}, qv);
       // key tiles 0,1 are done: the next unit's are requested into the same registers during the second pass
       // (after the last unit the current ones are fetched once more: harmless, and the code stays branch-free)
       pass(I2{}, I3{}, LAST, I0{}, I1{}, has_next ? nxt_u : cur_u);
       // ... and key tiles 2,3 right after it: they are needed last, half a sweep from now
+      if (prefetch_q) q_commit(qv, I1{}, qsmem + (buf ^ 1) * QBUF);
       if constexpr (last_rb) {
         issue_k(has_next ? nxt_u : cur_u, I2{}, I0{}, IKS{});
         issue_k(has_next ? nxt_u : cur_u, I3{}, I0{}, IKS{});
@@ -817,9 +879,17 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     for (int rb = 0; rb + 1 < a.nrb; ++rb) s2_block(rb, std::false_type{});
     s2_block(a.nrb - 1, std::true_type{});
     if (!LSE && has_next && !q_staged) stage_q(nxt_u, 0, qsmem + (buf ^ 1) * QBUF);
+    if (LSE && tid < 2) s_item[tid == 0 ? buf : 3] = 2 * kResidentGrid + drawn;  // (lane 1: the spare word)
     lds_barrier();  // cfr / stat and the Q buffers change hands
     PKV_T(4);
     cur_u = nxt_u;
+    if constexpr (LSE) {
+#ifdef PKV_RES_TIMING
+      tstamp[7] += 1;
+#endif
+      // (the word is written again two units from now, behind the next barrier: everyone has read it by then)
+      if (has_next) take(s_item[buf], nxt_u);
+    }
     buf ^= 1;
   }
 #ifdef PKV_RES_TIMING

@@ -184,7 +184,7 @@ def main():
                        "frac_of_hbm_peak": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "roofline": {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None if args.lse else measured_traffic(dominant, w.name, avg),
+                     "traffic": measured_traffic(dominant + ("_lse" if args.lse else ""), w.name, avg),
                      "algorithmic_bytes_per_launch": sweep_bytes, "avg_launch_ms": avg_ms[dominant],
                      "measured_read_GBps": read_gbps, "frac_of_measured_read": achieved / read_gbps},
         "kernel_ms_per_step": sum_ms,

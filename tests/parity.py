@@ -4,9 +4,11 @@ Protocol (fp32 device scores vs. fp64 oracle scores):
   * pooled scores agree within 1e-4 relative (+1e-30 absolute: fp32 flushes below its normal range);
   * the device's kept set is exactly the top-k (value desc, position asc) of the device's own scores,
     followed by the window -- checked with the oracle's selection routine, bit for bit;
-  * the kept set equals the oracle's bit for bit, unless the oracle's k-th and (k+1)-th values at the cut
-    differ by less than 1e-5 relative without being equal (a near-tie that fp32 cannot resolve); then the
-    two sets may differ only in positions whose oracle score is within 1e-5 relative of the cut value;
+  * the kept set equals the oracle's bit for bit, unless the oracle scores within 1e-5 relative of its k-th
+    value (the cut) take at least two distinct values (a near-tie that fp32 cannot resolve; with max pooling
+    the plateaus of two neighbouring sources can adjoin at the cut, so that the k-th and (k+1)-th values are
+    equal and the next distinct one is a hair away); then the two sets may differ only in positions inside
+    that band.  A band with a single value is an exact tie: the lower position wins, on both sides alike;
   * K_out / V_out rows are bit copies of K / V at the device's kept positions, and equal the oracle's
     K_out / V_out bit for bit whenever the kept sets agree.
 """
@@ -80,8 +82,9 @@ def compare_layer(Q, K, V, k_l, alpha, pool, pool_w, lens, gpu, ref=None, check_
             # sets differ: only allowed at an unresolved near-tie of the cut
             order = np.lexsort((np.arange(npre), -rp))
             vk, vk1 = rp[order[kk - 1]], rp[order[kk]]
-            assert vk != vk1 and (vk - vk1) <= TIE_RTOL * vk, (b, g, "kept set differs without a near-tie", vk, vk1)
+            band = np.abs(rp - vk) <= TIE_RTOL * vk
+            assert np.unique(rp[band]).size >= 2, (b, g, "kept set differs without a near-tie", vk, vk1)
             diff = np.setxor1d(gi[:kk], ri[:kk])
-            assert np.all(np.abs(rp[diff] - vk) <= TIE_RTOL * vk), (b, g, "difference outside the near-tie band")
+            assert np.all(band[diff]), (b, g, "difference outside the near-tie band")
             stats["near_tie_units"] += 1
     return stats

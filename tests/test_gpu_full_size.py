@@ -4,7 +4,8 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2406_02069_amd import binding, synth
+from oracle import pkv_oracle
+from paper_2406_02069_amd import binding, prefill_stub, synth
 from tests.parity import compare_layer
 
 pytestmark = pytest.mark.gpu
@@ -21,7 +22,9 @@ def _sample_layers(w, k):
     return out[:k]
 
 
-def _full(cfg, n_layers, avg=None):
+def _full(cfg, n_layers, avg=None, lse=False):
+    """lse: through pkv_compress_layers_lse with the denominators a prefill attention kernel would supply,
+    against the oracle given the same fp32 values."""
     w = synth.WORKLOADS[cfg]
     avg = avg or w.avg_budgets[0]
     ks = binding.budgets(w.L, avg, w.beta, w.alpha)
@@ -29,13 +32,23 @@ def _full(cfg, n_layers, avg=None):
     layers = [synth.make_layer(w, l, DEV) for l in sel]
     lens = layers[0][3]
     lens_dev = None if lens is None else torch.from_numpy(lens).to(DEV)
-    outs = binding.compress_layers([x[0] for x in layers], [x[1] for x in layers], [x[2] for x in layers],
-                                   [ks[l] for l in sel], w.pool, w.pool_w, seq_lens=lens_dev, want_scores=True)
+    Qs, Ks, Vs = [x[0] for x in layers], [x[1] for x in layers], [x[2] for x in layers]
+    if lse:
+        lses = [prefill_stub.window_lse(Q, K, lens) for Q, K in zip(Qs, Ks)]
+        outs = binding.compress_layers_lse(Qs, Ks, Vs, lses, [ks[l] for l in sel], w.pool, w.pool_w,
+                                           seq_lens=lens_dev, want_scores=True)
+    else:
+        outs = binding.compress_layers(Qs, Ks, Vs, [ks[l] for l in sel], w.pool, w.pool_w, seq_lens=lens_dev,
+                                       want_scores=True)
     torch.cuda.synchronize()
     tot = dict(units=0, near_tie_units=0)
-    for (Q, K, V, _), l, out in zip(layers, sel, outs):
-        print(f"config {cfg} layer {l} k_l {ks[l]}: oracle ...", flush=True)
-        st = compare_layer(Q, K, V, ks[l], w.alpha, w.pool, w.pool_w, lens, out)
+    for i, ((Q, K, V, _), l, out) in enumerate(zip(layers, sel, outs)):
+        print(f"config {cfg} layer {l} k_l {ks[l]} lse {lse}: oracle ...", flush=True)
+        ref = None
+        if lse:
+            ref = pkv_oracle.compress_layer(Q, K, V, ks[l], w.alpha, w.pool, w.pool_w, seq_lens=lens,
+                                            lse=np.nan_to_num(lses[i].cpu().numpy(), nan=0.0))
+        st = compare_layer(Q, K, V, ks[l], w.alpha, w.pool, w.pool_w, lens, out, ref=ref)
         print("   ", st, flush=True)
         tot["units"] += st["units"]
         tot["near_tie_units"] += st["near_tie_units"]
@@ -61,3 +74,15 @@ def test_config3_mistral_ragged_batch():
 
 def test_config4_llama3_70b_32k():
     _full(4, 1)
+
+
+def test_config2_llama3_8b_32k_supplied_denominators():
+    _full(2, 2, lse=True)
+
+
+def test_config3_mistral_ragged_batch_supplied_denominators():
+    _full(3, 1, lse=True)
+
+
+def test_config4_llama3_70b_32k_supplied_denominators():
+    _full(4, 1, lse=True)

@@ -17,7 +17,8 @@
  * closed forms of the budget sequence; for the variant with supplied softmax
  * denominators: a library log-sum-exp reproduces the plain softmax, the
  * closed form exp(-ln c) = 1/c for all-zero logits, and the exp(-delta)
- * scaling of a row whose denominator is shifted.  The integer rounding of the budgets,
+ * scaling of a row whose denominator is shifted; for the paged output: a
+ * hand-written pool image and the identity table.  The integer rounding of the budgets,
  * the pool padding rule and the GQA mean are conventions the paper does not
  * fix ("parity unpinned" by the paper; pinned only to the stated reading).
  *
@@ -371,6 +372,49 @@ int pkvo_compress_layer_lse(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
   return compress_layer_impl(B, Hq, Hkv, d, N, alpha, k_l, pool, pool_w, Q_win,
                              K, V, seq_lens, lse, K_out, V_out, idx_out,
                              count_out, pooled_out);
+}
+
+/* ------------------------------------------------------------------------
+ * Per-layer paged output (appendix "PyramidKV Implementation at vLLM": every
+ * layer has its own block table, because every layer keeps a different number
+ * of tokens).  The kept rows of sequence b (K_out / V_out of
+ * pkvo_compress_layer, rows 0 .. count_b-1) are written to the layer's page
+ * pool:
+ *   row j of KV head g  ->  page table[b][j / P], head g, slot j % P
+ *   K_pages, V_pages : [num_pages][Hkv][P][d], only the kept rows are written
+ *   table            : [B][max_pages] page numbers
+ * Returns 0; 1 for invalid arguments; 2 if a needed table entry is outside
+ * [0, num_pages) or the table is too short (nothing is written then).
+ * ---------------------------------------------------------------------- */
+int pkvo_scatter_pages(int32_t B, int32_t Hkv, int32_t d, int32_t k_cap,
+                       int32_t P, int32_t num_pages, int32_t max_pages,
+                       const uint16_t *K_out, const uint16_t *V_out,
+                       const int32_t *count, const int32_t *table,
+                       uint16_t *K_pages, uint16_t *V_pages) {
+  if (B < 1 || Hkv < 1 || d < 1 || k_cap < 1 || P < 1 || num_pages < 1 ||
+      max_pages < 1 || !K_out || !V_out || !count || !table || !K_pages ||
+      !V_pages)
+    return 1;
+  for (int32_t b = 0; b < B; ++b) {
+    if (count[b] < 0 || count[b] > k_cap) return 1;
+    const int32_t need = (count[b] + P - 1) / P;
+    if (need > max_pages) return 2;
+    for (int32_t q = 0; q < need; ++q) {
+      const int32_t pg = table[(size_t)b * max_pages + q];
+      if (pg < 0 || pg >= num_pages) return 2;
+    }
+  }
+  for (int32_t b = 0; b < B; ++b)
+    for (int32_t g = 0; g < Hkv; ++g)
+      for (int32_t j = 0; j < count[b]; ++j) {
+        const int32_t pg = table[(size_t)b * max_pages + j / P];
+        const size_t src = (((size_t)b * Hkv + g) * k_cap + j) * (size_t)d;
+        const size_t dst =
+            ((((size_t)pg * Hkv + g) * P) + (size_t)(j % P)) * (size_t)d;
+        memcpy(K_pages + dst, K_out + src, sizeof(uint16_t) * (size_t)d);
+        memcpy(V_pages + dst, V_out + src, sizeof(uint16_t) * (size_t)d);
+      }
+  return 0;
 }
 
 /* Number of OpenMP threads the scoring loop will use (for reports). */

@@ -45,6 +45,8 @@ def _load():
         lib.pkvo_window_scores_lse.argtypes = [i32, i32, i32, i32, p, p, p, p, p]
         lib.pkvo_compress_layer.argtypes = [i32] * 9 + [p] * 9
         lib.pkvo_compress_layer_lse.argtypes = [i32] * 9 + [p] * 10
+        lib.pkvo_scatter_pages.argtypes = [i32] * 7 + [p] * 6
+        lib.pkvo_scatter_pages.restype = ctypes.c_int
         for f in (lib.pkvo_budgets, lib.pkvo_window_scores, lib.pkvo_window_scores_lse, lib.pkvo_pool,
                   lib.pkvo_topk, lib.pkvo_compress_layer, lib.pkvo_compress_layer_lse,
                   lib.pkvo_num_threads):
@@ -157,3 +159,21 @@ def compress_layer(Q_win, K, V, k_l: int, alpha: int, pool_kind: int, pool_w: in
     if rc != 0:
         raise ValueError("pkvo_compress_layer: invalid arguments")
     return dict(K_out=K_out, V_out=V_out, idx=idx, count=count, pooled=pooled)
+
+
+def scatter_pages(K_out: np.ndarray, V_out: np.ndarray, count: np.ndarray, table: np.ndarray, page_size: int,
+                  K_pages: np.ndarray, V_pages: np.ndarray):
+    """Kept rows (K_out, V_out uint16 [B,Hkv,k_cap,d], count [B]) into copies of the page pools
+    (uint16 [num_pages,Hkv,page_size,d]) through the block table (int32 [B,max_pages]).  Returns the new pools."""
+    K_out, V_out = np.ascontiguousarray(K_out), np.ascontiguousarray(V_out)
+    B, Hkv, k_cap, d = K_out.shape
+    count = np.ascontiguousarray(count, dtype=np.int32)
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    Kp, Vp = np.array(K_pages, dtype=np.uint16, order="C"), np.array(V_pages, dtype=np.uint16, order="C")
+    num_pages = Kp.shape[0]
+    assert Kp.shape == (num_pages, Hkv, page_size, d) == Vp.shape and table.shape[0] == B
+    rc = _load().pkvo_scatter_pages(B, Hkv, d, k_cap, page_size, num_pages, table.shape[1], _ptr(K_out), _ptr(V_out),
+                                    _ptr(count), _ptr(table), _ptr(Kp), _ptr(Vp))
+    if rc != 0:
+        raise ValueError(f"pkvo_scatter_pages: status {rc}")
+    return Kp, Vp

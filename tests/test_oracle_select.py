@@ -154,3 +154,44 @@ def test_uniform_budget_nesting_across_a_budget_sweep():
         cur = set(int(i) for i in out["idx"][0, 0])
         assert prev is None or prev <= cur
         prev = cur
+
+
+# ---- per-layer paged output (appendix "PyramidKV Implementation at vLLM") -------------------------------
+
+
+def test_scatter_pages_hand_written_pool_image():
+    # one sequence, one head, d = 2: five kept rows, pages of two slots, block table [3, 0, 2] into a pool of four
+    # pages.  Rows 0,1 -> page 3; rows 2,3 -> page 0; row 4 -> page 2 slot 0; everything else keeps its old content.
+    K_out = np.array([[[[10, 11], [20, 21], [30, 31], [40, 41], [50, 51], [0, 0]]]], dtype=np.uint16)
+    V_out = K_out + 100
+    pool = np.full((4, 1, 2, 2), 7, dtype=np.uint16)
+    Kp, Vp = pkv_oracle.scatter_pages(K_out, V_out, np.array([5]), np.array([[3, 0, 2]]), 2, pool, pool)
+    want = np.array([[[[30, 31], [40, 41]]], [[[7, 7], [7, 7]]], [[[50, 51], [7, 7]]], [[[10, 11], [20, 21]]]],
+                    dtype=np.uint16)
+    np.testing.assert_array_equal(Kp, want)
+    np.testing.assert_array_equal(Vp, np.where(want == 7, 7, want + 100))
+    np.testing.assert_array_equal(pool, 7)                           # the inputs are not modified
+
+
+def test_scatter_pages_identity_table_and_heads():
+    # pages numbered in order and as large as the budget: the pool is the compact cache, head by head
+    rs = np.random.RandomState(3)
+    B, Hkv, k_cap, d = 3, 2, 8, 4
+    K_out = rs.randint(1, 60000, size=(B, Hkv, k_cap, d)).astype(np.uint16)
+    V_out = rs.randint(1, 60000, size=(B, Hkv, k_cap, d)).astype(np.uint16)
+    count = np.array([8, 5, 0])
+    pool = np.zeros((B, Hkv, k_cap, d), dtype=np.uint16)
+    Kp, Vp = pkv_oracle.scatter_pages(K_out, V_out, count, np.arange(B)[:, None], k_cap, pool, pool)
+    for b in range(B):
+        np.testing.assert_array_equal(Kp[b, :, : count[b]], K_out[b, :, : count[b]])
+        np.testing.assert_array_equal(Vp[b, :, : count[b]], V_out[b, :, : count[b]])
+        assert not Kp[b, :, count[b]:].any() and not Vp[b, :, count[b]:].any()
+
+
+def test_scatter_pages_rejects_bad_tables():
+    K_out = np.ones((1, 1, 4, 2), dtype=np.uint16)
+    pool = np.zeros((2, 1, 2, 2), dtype=np.uint16)
+    with pytest.raises(ValueError):
+        pkv_oracle.scatter_pages(K_out, K_out, np.array([4]), np.array([[0, 2]]), 2, pool, pool)     # page 2 of 2
+    with pytest.raises(ValueError):
+        pkv_oracle.scatter_pages(K_out, K_out, np.array([4]), np.array([[0]]), 2, pool, pool)        # table too short

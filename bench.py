@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--lse", action="store_true",
                     help="variant: one-sweep scoring with the window queries' softmax denominators supplied "
                          "(computed beforehand, outside the timed region); not the headline configuration")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="variant: kept rows written into per-layer page pools of this page size through random "
+                         "block tables (pkv_compress_layers_paged); not the headline configuration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -103,7 +106,7 @@ def main():
     lens_dev = None if lens is None else torch.from_numpy(lens).to(dev)
 
     # all layers resident in HBM; a bounded set of layers is also kept on the host for the oracle
-    if args.lse:
+    if args.lse or args.page_size > 0:
         args.no_cpu_baseline = True
     n_host = 0 if args.no_cpu_baseline else min(w.L, 32)
     host_ids = sorted(set([0, w.L - 1] + list(range(1, w.L - 1))[: max(n_host - 2, 0)])) if n_host else []
@@ -117,7 +120,18 @@ def main():
     if args.lse:  # what the prefill attention kernel would hand over; an input, prepared before timing
         from paper_2406_02069_amd import prefill_stub
         lses = [prefill_stub.window_lse(Qs[l], Ks[l], lens) for l in range(w.L)]
-    call = binding.LayersCall(Qs, Ks, Vs, ks, w.pool, w.pool_w, seq_lens=lens_dev, lse=lses)
+    paged = None
+    if args.page_size > 0:  # every layer its own pool and block table; pages handed out in a seeded random order
+        P = args.page_size
+        max_pages = max((min(k, w.N) + P - 1) // P for k in ks)
+        num_pages = w.B * max_pages
+        rs = np.random.RandomState(1234)
+        Kp = [torch.zeros(num_pages, w.Hkv, P, w.d, dtype=torch.bfloat16, device=dev) for _ in range(w.L)]
+        Vp = [torch.zeros(num_pages, w.Hkv, P, w.d, dtype=torch.bfloat16, device=dev) for _ in range(w.L)]
+        tbs = [torch.from_numpy(rs.permutation(num_pages).astype(np.int32).reshape(w.B, max_pages)).to(dev)
+               for _ in range(w.L)]
+        paged = (Kp, Vp, tbs, P)
+    call = binding.LayersCall(Qs, Ks, Vs, ks, w.pool, w.pool_w, seq_lens=lens_dev, lse=lses, paged=paged)
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -165,7 +179,8 @@ def main():
     achieved = sweep_bytes / (avg_ms[dominant] * 1e-3) / 1e9
     out = {
         "metric": "compressed prefill tokens/sec (all layers, select+gather); achieved HBM GB/s" +
-                  (" [variant: softmax denominators supplied, one sweep]" if args.lse else ""),
+                  (" [variant: softmax denominators supplied, one sweep]" if args.lse else "") +
+                  (f" [variant: paged output, page size {args.page_size}]" if args.page_size > 0 else ""),
         "value": sum_n / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -178,7 +193,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B{w.B} L{w.L} Hq{w.Hq} Hkv{w.Hkv} d{w.d} N{w.N} alpha{w.alpha} "
-                               f"avg_budget{avg} beta{w.beta} pool{w.pool}/w{w.pool_w}" + (" +lse" if args.lse else ""),
+                               f"avg_budget{avg} beta{w.beta} pool{w.pool}/w{w.pool_w}" + (" +lse" if args.lse else "") + (f" +pages{args.page_size}" if args.page_size > 0 else ""),
                    "tokens_per_step": sum_n, "algorithmic_bytes_per_step": total_bytes},
         "whole_path": {"achieved_GBps": total_bytes / (ms_per_step * 1e-3) / 1e9,
                        "frac_of_hbm_peak": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS},

@@ -218,10 +218,60 @@ int pkv_compress_layers_lse(int32_t L, const pkv_layer_desc* descs,
                             size_t workspace_bytes, void* stream);
 
 /*
+ * Per-layer paged output (appendix "PyramidKV Implementation at vLLM": every
+ * layer keeps a different number of tokens, so every layer gets its own
+ * block table and page pool instead of a share of one uniform paged cache).
+ * As pkv_compress_layers (lse NULL) or pkv_compress_layers_lse (lse given),
+ * except that the kept rows go straight into pages:
+ *   kept row j (0 <= j < count_b) of sequence b, KV head g, layer l
+ *     -> K_pages[l] / V_pages[l], page block_tables[l][b][j / page_size],
+ *        head g, slot j % page_size.
+ * Nothing else in the pools is written (a partly filled last page keeps its
+ * old content behind the kept rows); descs[l].o_* are checked as usual but
+ * not used.
+ */
+typedef struct {
+  int32_t page_size; /* tokens per page, >= 1                                */
+  int32_t num_pages; /* pages in each layer's pool                           */
+  int32_t max_pages; /* entries per sequence in each block table,
+                        >= ceil(min(k_l, N) / page_size) for every layer     */
+  int32_t reserved;  /* must be 0                                            */
+} pkv_paged_desc;
+
+/*
+ * paged        HOST.
+ * K_pages, V_pages
+ *              HOST arrays of L DEVICE pointers, each bf16
+ *              [num_pages, Hkv, page_size, d] contiguous, 16-byte aligned.
+ * block_tables HOST array of L DEVICE pointers, each int32 [B, max_pages]
+ *              contiguous: page numbers in [0, num_pages).  Entries beyond
+ *              ceil(count_b / page_size) are not read.  A page number out of
+ *              range is never written through: the row is dropped and
+ *              count_out[l][b] is set to -2.
+ * idx_out, count_out, scores_out, seq_lens, workspace, stream: as
+ * pkv_compress_layers.
+ * Errors: as pkv_compress_layers(_lse); paged NULL or inconsistent (sizes
+ * < 1, reserved != 0, max_pages too small for a layer's budget), a NULL or
+ * misaligned table -> PKV_ERR_INVALID_ARG.
+ */
+int pkv_compress_layers_paged(int32_t L, const pkv_layer_desc* descs,
+                              const void* const* Q_win, const void* const* K,
+                              const void* const* V, const float* const* lse,
+                              const int32_t* seq_lens,
+                              const pkv_paged_desc* paged,
+                              void* const* K_pages, void* const* V_pages,
+                              const int32_t* const* block_tables,
+                              int32_t* const* idx_out,
+                              int32_t* const* count_out,
+                              float* const* scores_out, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid (no part of the method): pkv_compress_layers (lse NULL)
- * or pkv_compress_layers_lse (lse given) with the caller's HIP events
- * recorded around the kernels, so that a benchmark can attribute device time
- * to each kernel without a profiler.
+ * or pkv_compress_layers_lse (lse given), compact (paged NULL) or paged
+ * output (paged and block_tables given; K_out / V_out are then the page
+ * pools), with the caller's HIP events recorded around the kernels, so that
+ * a benchmark can attribute device time to each kernel without a profiler.
  *
  * events     HOST array of n_events hipEvent_t handles created by the caller
  *            with timing enabled.  events[0] is recorded on `stream` before
@@ -246,7 +296,8 @@ typedef enum {
 int pkv_compress_layers_profiled(
     int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
     const void* const* K, const void* const* V, const float* const* lse,
-    const int32_t* seq_lens,
+    const int32_t* seq_lens, const pkv_paged_desc* paged,
+    const int32_t* const* block_tables,
     void* const* K_out, void* const* V_out, int32_t* const* idx_out,
     int32_t* const* count_out, float* const* scores_out, void* workspace,
     size_t workspace_bytes, void* stream, void* const* events,

@@ -20,7 +20,7 @@ POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers",
-           "pkv_compress_layers_lse", "pkv_compress_layers_profiled", "pkv_probe_read", "pkv_status_string"]
+           "pkv_compress_layers_lse", "pkv_compress_layers_paged", "pkv_compress_layers_profiled", "pkv_probe_read", "pkv_status_string"]
 
 
 class PkvError(RuntimeError):
@@ -34,6 +34,10 @@ class LayerDesc(ctypes.Structure):
                 ("B", "Hq", "Hkv", "d", "N", "alpha", "k_l", "pool", "pool_w", "reserved")] + \
                [(n, ctypes.c_int64) for n in
                 ("q_sb", "q_sh", "q_st", "kv_sb", "kv_sh", "kv_st", "o_sb", "o_sh", "o_st")]
+
+
+class PagedDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("page_size", "num_pages", "max_pages", "reserved")]
 
 
 _lib = None
@@ -57,6 +61,9 @@ def load() -> ctypes.CDLL:
         lib.pkv_compress_layers.restype = ctypes.c_int
         lib.pkv_compress_layers_lse.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 11 + [ctypes.c_size_t, vp]
         lib.pkv_compress_layers_lse.restype = ctypes.c_int
+        lib.pkv_compress_layers_paged.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 5 + \
+            [ctypes.POINTER(PagedDesc)] + [vp] * 6 + [vp, ctypes.c_size_t, vp]
+        lib.pkv_compress_layers_paged.restype = ctypes.c_int
         lib.pkv_status_string.argtypes = [ctypes.c_int]
         lib.pkv_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -155,7 +162,10 @@ class LayersCall:
 
     def __init__(self, Q_win: Sequence[torch.Tensor], K: Sequence[torch.Tensor], V: Sequence[torch.Tensor],
                  k_ls: Sequence[int], pool: int, pool_w: int, seq_lens: Optional[torch.Tensor] = None,
-                 want_scores: bool = False, lse: Optional[Sequence[torch.Tensor]] = None):
+                 want_scores: bool = False, lse: Optional[Sequence[torch.Tensor]] = None, paged=None):
+        """paged: None, or (K_pages, V_pages, block_tables, page_size): per layer bf16 pools
+        [num_pages, Hkv, page_size, d] and int32 tables [B, max_pages]; the kept rows then go into the pools
+        (pkv_compress_layers_paged) and the first two entries of every output tuple are the layer's pools."""
         L = len(K)
         assert len(Q_win) == L and len(V) == L and len(k_ls) == L
         self.L = L
@@ -182,8 +192,30 @@ class LayersCall:
             self.inputs = self.inputs + (list(lse),)
             self._lse = ptrs(lse)
 
+        self._paged = None
+        if paged is not None:
+            Kp, Vp, tables, page_size = paged
+            assert len(Kp) == L and len(Vp) == L and len(tables) == L
+            B, Hkv, d = K[0].shape[0], K[0].shape[1], K[0].shape[3]
+            num_pages, max_pages = Kp[0].shape[0], tables[0].shape[1]
+            for l in range(L):
+                assert Kp[l].dtype == torch.bfloat16 and Kp[l].is_contiguous() and Vp[l].is_contiguous()
+                assert tuple(Kp[l].shape) == (num_pages, Hkv, page_size, d) == tuple(Vp[l].shape)
+                assert tables[l].dtype == torch.int32 and tables[l].is_contiguous()
+                assert tuple(tables[l].shape) == (B, max_pages)
+            self.inputs = self.inputs + (list(Kp), list(Vp), list(tables))
+            self._paged = (PagedDesc(page_size, num_pages, max_pages, 0), ptrs(Kp), ptrs(Vp), ptrs(tables))
+            self.outputs = [(Kp[l], Vp[l]) + tuple(o[2:]) for l, o in enumerate(self.outputs)]
+
     def run(self):
         tail = (_p(self.workspace), self.workspace.numel(), _stream_ptr(self.device))
+        if self._paged is not None:
+            a, (pd, kp, vp, tb) = self._args, self._paged
+            rc = load().pkv_compress_layers_paged(self.L, self.descs, a[0], a[1], a[2], self._lse, a[3],
+                                                  ctypes.byref(pd), kp, vp, tb, a[6], a[7], a[8], *tail)
+            if rc != OK:
+                raise PkvError(rc, "pkv_compress_layers_paged")
+            return self.outputs
         if self._lse is not None:
             a = self._args
             rc = load().pkv_compress_layers_lse(self.L, self.descs, a[0], a[1], a[2], self._lse, *a[3:], *tail)
@@ -203,6 +235,13 @@ def compress_layers_lse(Q_win, K, V, lse, k_ls, pool, pool_w, seq_lens=None, wan
     """pkv_compress_layers_lse: the same with the window queries' softmax denominators supplied per layer
     (fp32 [B, Hq, alpha] each)."""
     return LayersCall(Q_win, K, V, k_ls, pool, pool_w, seq_lens, want_scores, lse=lse).run()
+
+
+def compress_layers_paged(Q_win, K, V, k_ls, pool, pool_w, K_pages, V_pages, block_tables, page_size,
+                          seq_lens=None, want_scores=False, lse=None):
+    """pkv_compress_layers_paged: kept rows written into per-layer page pools through per-layer block tables."""
+    return LayersCall(Q_win, K, V, k_ls, pool, pool_w, seq_lens, want_scores, lse=lse,
+                      paged=(K_pages, V_pages, block_tables, page_size)).run()
 
 
 def probe_read(buf: torch.Tensor, sink: torch.Tensor) -> None:
@@ -254,14 +293,18 @@ def run_profiled(call: LayersCall, events: HipEvents):
     lib = load()
     if not hasattr(lib, "_prof_ready"):
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
-        lib.pkv_compress_layers_profiled.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 11 + \
+        lib.pkv_compress_layers_profiled.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 5 + \
+            [ctypes.POINTER(PagedDesc), vp] + [vp] * 6 + \
             [ctypes.c_size_t, vp, vp, i32, vp, vp]
         lib.pkv_compress_layers_profiled.restype = ctypes.c_int
         lib._prof_ready = True
     ids = (ctypes.c_int32 * events.n)()
     used = ctypes.c_int32(0)
     a = call._args
-    rc = lib.pkv_compress_layers_profiled(call.L, call.descs, a[0], a[1], a[2], call._lse, *a[3:], _p(call.workspace),
+    pd, kp, vp_, tb = call._paged if call._paged is not None else (None, a[4], a[5], None)
+    rc = lib.pkv_compress_layers_profiled(call.L, call.descs, a[0], a[1], a[2], call._lse, a[3],
+                                          None if pd is None else ctypes.byref(pd), tb, kp, vp_, a[6], a[7], a[8],
+                                          _p(call.workspace),
                                           call.workspace.numel(), _stream_ptr(call.device), events.handles,
                                           events.n, ids, ctypes.byref(used))
     if rc != OK:

@@ -96,6 +96,7 @@ struct LayerPtrs {
   int32_t* count_out;
   float* scores_out;
   const float* lse;  // supplied softmax denominators, or null
+  const int32_t* table;  // paged output: the layer's block table (K_out, V_out are then the page pools), or null
 };
 
 static int check_ptrs(const LayerPtrs& p) {
@@ -104,7 +105,7 @@ static int check_ptrs(const LayerPtrs& p) {
     return PKV_ERR_INVALID_ARG;
   if (((uintptr_t)p.idx_out & 3) || ((uintptr_t)p.count_out & 3) || ((uintptr_t)p.scores_out & 3))
     return PKV_ERR_INVALID_ARG;
-  if ((uintptr_t)p.lse & 3) return PKV_ERR_INVALID_ARG;
+  if (((uintptr_t)p.lse & 3) || ((uintptr_t)p.table & 3)) return PKV_ERR_INVALID_ARG;
   return PKV_OK;
 }
 
@@ -166,7 +167,8 @@ static bool use_resident(const Plan& plan, bool lse_mode) {
 
 // Queue the kernels of L layers.  All arguments have been validated.
 static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, const LayerPtrs* ptrs,
-                      const int32_t* seq_lens, void* workspace, hipStream_t stream, Recorder* rec) {
+                      const int32_t* seq_lens, void* workspace, hipStream_t stream, Recorder* rec,
+                      const pkv_paged_desc* paged) {
   const pkv_layer_desc& d = descs[0];
   char* ws = static_cast<char*>(workspace);
   float* raw = reinterpret_cast<float*>(ws + plan.off_raw);
@@ -271,6 +273,8 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       ga.layer[i].K_out = static_cast<uint16_t*>(ptrs[l].K_out);
       ga.layer[i].V_out = static_cast<uint16_t*>(ptrs[l].V_out);
       ga.layer[i].idx = ptrs[l].idx_out;
+      ga.layer[i].table = ptrs[l].table;
+      ga.layer[i].count_out = ptrs[l].count_out;
       ga.layer[i].o_sb = descs[l].o_sb; ga.layer[i].o_sh = descs[l].o_sh; ga.layer[i].o_st = descs[l].o_st;
       ga.layer[i].k_cap = k_cap;
     }
@@ -287,6 +291,9 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
     se.err = (any_scores && resident) ? reinterpret_cast<const int32_t*>(ws + plan.off_cnt) : nullptr;
     ga.L = nl; ga.B = d.B; ga.Hkv = d.Hkv; ga.d = d.d; ga.k_cap_max = k_cap_max; ga.N = d.N;
     ga.kv_sb = d.kv_sb; ga.kv_sh = d.kv_sh; ga.kv_st = d.kv_st;
+    if (paged) {
+      ga.page_size = paged->page_size; ga.num_pages = paged->num_pages; ga.max_pages = paged->max_pages;
+    }
     if (launch_pool_select_batch(se, nl, stream) != hipSuccess) return PKV_ERR_HIP;
     if (rec) rec->after(PKV_KERNEL_POOL_SELECT, stream);
     if (launch_gather_batch(ga, stream) != hipSuccess) return PKV_ERR_HIP;
@@ -300,10 +307,15 @@ static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const vo
                                 void* const* K_out, void* const* V_out, int32_t* const* idx_out,
                                 int32_t* const* count_out, float* const* scores_out, void* workspace,
                                 size_t workspace_bytes, void* stream, Recorder* rec,
-                                const float* const* lse = nullptr, bool want_lse = false) {
+                                const float* const* lse = nullptr, bool want_lse = false,
+                                const pkv_paged_desc* paged = nullptr, const int32_t* const* tables = nullptr) {
   if (L < 1 || L > kMaxLayers || !descs || !Q_win || !K || !V || !K_out || !V_out || !idx_out || !count_out)
     return PKV_ERR_INVALID_ARG;
   if (want_lse && !lse) return PKV_ERR_INVALID_ARG;
+  if (paged) {
+    if (!tables || paged->page_size < 1 || paged->num_pages < 1 || paged->max_pages < 1 || paged->reserved != 0)
+      return PKV_ERR_INVALID_ARG;
+  }
   if ((uintptr_t)seq_lens & 3) return PKV_ERR_INVALID_ARG;
   LayerPtrs ptrs[kMaxLayers];
   for (int32_t l = 0; l < L; ++l) {
@@ -315,8 +327,13 @@ static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const vo
         a.kv_sb != b.kv_sb || a.kv_sh != b.kv_sh || a.kv_st != b.kv_st)
       return PKV_ERR_INVALID_ARG;
     ptrs[l] = {Q_win[l], K[l], V[l], K_out[l], V_out[l], idx_out[l], count_out[l],
-               scores_out ? scores_out[l] : nullptr, want_lse ? lse[l] : nullptr};
+               scores_out ? scores_out[l] : nullptr, want_lse ? lse[l] : nullptr, paged ? tables[l] : nullptr};
     if (want_lse && !ptrs[l].lse) return PKV_ERR_INVALID_ARG;
+    if (paged) {  // the block table must reach as far as this layer's budget
+      if (!ptrs[l].table) return PKV_ERR_INVALID_ARG;
+      const int64_t k_cap = descs[l].k_l < descs[l].N ? descs[l].k_l : descs[l].N;
+      if ((k_cap + paged->page_size - 1) / paged->page_size > paged->max_pages) return PKV_ERR_INVALID_ARG;
+    }
     rc = check_ptrs(ptrs[l]);
     if (rc != PKV_OK) return rc;
   }
@@ -328,7 +345,7 @@ static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const vo
     for (int32_t i = 0; i < 5 * L + 1; ++i)
       if (!rec->events[i]) return PKV_ERR_INVALID_ARG;
   }
-  return run_layers(L, descs, plan, ptrs, seq_lens, workspace, static_cast<hipStream_t>(stream), rec);
+  return run_layers(L, descs, plan, ptrs, seq_lens, workspace, static_cast<hipStream_t>(stream), rec, paged);
 }
 
 }  // namespace pkv
@@ -403,9 +420,21 @@ int pkv_compress_layers_lse(int32_t L, const pkv_layer_desc* descs, const void* 
                               workspace, workspace_bytes, stream, nullptr, lse, true);
 }
 
+int pkv_compress_layers_paged(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win, const void* const* K,
+                              const void* const* V, const float* const* lse, const int32_t* seq_lens,
+                              const pkv_paged_desc* paged, void* const* K_pages, void* const* V_pages,
+                              const int32_t* const* block_tables, int32_t* const* idx_out,
+                              int32_t* const* count_out, float* const* scores_out, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (!paged) return PKV_ERR_INVALID_ARG;
+  return compress_layers_impl(L, descs, Q_win, K, V, seq_lens, K_pages, V_pages, idx_out, count_out, scores_out,
+                              workspace, workspace_bytes, stream, nullptr, lse, lse != nullptr, paged, block_tables);
+}
+
 int pkv_compress_layers_profiled(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
                                  const void* const* K, const void* const* V, const float* const* lse,
-                                 const int32_t* seq_lens,
+                                 const int32_t* seq_lens, const pkv_paged_desc* paged,
+                                 const int32_t* const* block_tables,
                                  void* const* K_out, void* const* V_out, int32_t* const* idx_out,
                                  int32_t* const* count_out, float* const* scores_out, void* workspace,
                                  size_t workspace_bytes, void* stream, void* const* events, int32_t n_events,
@@ -413,7 +442,8 @@ int pkv_compress_layers_profiled(int32_t L, const pkv_layer_desc* descs, const v
   if (!n_used) return PKV_ERR_INVALID_ARG;
   Recorder rec = {events, n_events, kernel_ids, 0};
   const int rc = compress_layers_impl(L, descs, Q_win, K, V, seq_lens, K_out, V_out, idx_out, count_out,
-                                      scores_out, workspace, workspace_bytes, stream, &rec, lse, lse != nullptr);
+                                      scores_out, workspace, workspace_bytes, stream, &rec, lse, lse != nullptr,
+                                      paged, block_tables);
   *n_used = rec.used;
   return rc;
 }

@@ -5,6 +5,10 @@
 // A row is 2*d bytes (128 or 256); d/8 neighbouring lanes move one row with 16-byte accesses, so both
 // the read of a kept row and the write of the compact row are fully coalesced.  All layers of a call
 // are served by one launch (grid.z = layer).  This is the only place where V is touched.
+//
+// Paged output (appendix "PyramidKV Implementation at vLLM": one block table per layer, since every layer keeps a
+// different number of tokens): kept row j of head g goes to page table[b][j / P], head g, slot j % P of the
+// layer's pool [num_pages][Hkv][P][d]; nothing else in the pool is written.
 #include "pkv_internal.h"
 
 namespace pkv {
@@ -21,6 +25,20 @@ __global__ __launch_bounds__(256) void gather_batch_kernel(const GatherBatchArgs
   const int j = t / LPR, seg = t - j * LPR;
   if (j >= ly.k_cap) return;
   const int src = ly.idx[(size_t)bg * ly.k_cap + j];
+  if (a.page_size > 0) {
+    if ((uint32_t)src >= (uint32_t)a.N) return;  // unused slot: the pool keeps its content
+    const int q = j / a.page_size, slot = j - q * a.page_size;
+    const int pg = q < a.max_pages ? ly.table[(size_t)b * a.max_pages + q] : -1;
+    if ((uint32_t)pg >= (uint32_t)a.num_pages) {  // never written through a bad page number: reported instead
+      ly.count_out[b] = -2;
+      return;
+    }
+    const size_t off = (size_t)b * a.kv_sb + (size_t)g * a.kv_sh + (size_t)src * a.kv_st + seg * 8;
+    const size_t o = (((size_t)pg * a.Hkv + g) * a.page_size + slot) * D + seg * 8;
+    *reinterpret_cast<uint4*>(ly.K_out + o) = *reinterpret_cast<const uint4*>(ly.K + off);
+    *reinterpret_cast<uint4*>(ly.V_out + o) = *reinterpret_cast<const uint4*>(ly.V + off);
+    return;
+  }
   uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
   if ((uint32_t)src < (uint32_t)a.N) {  // -1 marks an unused slot; anything else out of range is not dereferenced either
     const size_t off = (size_t)b * a.kv_sb + (size_t)g * a.kv_sh + (size_t)src * a.kv_st + seg * 8;

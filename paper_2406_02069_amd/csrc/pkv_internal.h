@@ -124,6 +124,8 @@ struct GatherLayer {
   uint16_t* K_out;
   uint16_t* V_out;
   const int32_t* idx;
+  const int32_t* table;  // paged output: [B][max_pages] page numbers of this layer, else null
+  int32_t* count_out;    // paged output: [B], set to -2 where a page number is out of range
   int64_t o_sb, o_sh, o_st;
   int32_t k_cap, pad;
 };
@@ -132,6 +134,7 @@ struct GatherBatchArgs {
   GatherLayer layer[kBatchMaxLayers];
   int32_t L, B, Hkv, d, k_cap_max;
   int32_t N;  // rows per head in K and V: positions outside [0, N) are never dereferenced
+  int32_t page_size, num_pages, max_pages;  // page_size 0: compact output through the o_* strides
   int64_t kv_sb, kv_sh, kv_st;
 };
 

@@ -145,3 +145,24 @@ def test_compress_layers_lse_rejects_missing_or_misaligned_denominators():
     assert call((ctypes.c_void_p * 2)(0x1000, None)) == I          # a layer without them
     assert call((ctypes.c_void_p * 2)(0x1000, 0x2002)) == I        # not 4-byte aligned
     assert call(arr, ws_bytes=16) == binding.ERR_WORKSPACE         # valid so far: fails at the workspace check
+
+
+def test_compress_layers_paged_rejects_inconsistent_paging():
+    lib = binding.load()
+    descs = (binding.LayerDesc * 2)(_desc(k_l=128), _desc(k_l=64))
+    arr = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    I = binding.ERR_INVALID_ARG
+
+    def call(pd, tables=arr, ws_bytes=16):
+        pdp = None if pd is None else ctypes.byref(pd)
+        return lib.pkv_compress_layers_paged(2, descs, arr, arr, arr, None, None, pdp, arr, arr, tables, arr, arr,
+                                             None, 0x10000, ws_bytes, None)
+
+    assert call(None) == I                                              # no paging descriptor
+    assert call(binding.PagedDesc(0, 8, 8, 0)) == I                     # page size
+    assert call(binding.PagedDesc(16, 0, 8, 0)) == I                    # empty pool
+    assert call(binding.PagedDesc(16, 8, 8, 1)) == I                    # reserved
+    assert call(binding.PagedDesc(16, 64, 7, 0)) == I                   # 128 kept rows need 8 table entries
+    assert call(binding.PagedDesc(16, 64, 8, 0), tables=None) == I      # no tables
+    assert call(binding.PagedDesc(16, 64, 8, 0), tables=(ctypes.c_void_p * 2)(0x1000, 0x2002)) == I
+    assert call(binding.PagedDesc(16, 64, 8, 0)) == binding.ERR_WORKSPACE   # valid so far

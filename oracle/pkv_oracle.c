@@ -18,7 +18,10 @@
  * denominators: a library log-sum-exp reproduces the plain softmax, the
  * closed form exp(-ln c) = 1/c for all-zero logits, and the exp(-delta)
  * scaling of a row whose denominator is shifted; for the paged output: a
- * hand-written pool image and the identity table.  The integer rounding of the budgets,
+ * hand-written pool image and the identity table; for the attention recall:
+ * everything kept gives 1, identical keys give a harmonic closed form, and
+ * the kept mass equals the sum of the window scores at the kept positions;
+ * for the geometric schedule: its defining ratios and sum.  The integer rounding of the budgets,
  * the pool padding rule and the GQA mean are conventions the paper does not
  * fix ("parity unpinned" by the paper; pinned only to the stated reading).
  *
@@ -86,6 +89,56 @@ int pkvo_budgets(int32_t L, int32_t avg, int32_t beta, int32_t alpha,
   }
   for (int32_t l = 0; l < L; ++l) k_out[l] += alpha;
   free(rem);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Other allocation strategies of the ablation (appendix "Allocation
+ * Strategies"): the paper names a geometric and an exponential decay beside
+ * the linear one and gives no formula for either.  Written in the layer
+ * index both are r_l = C * q^l, so one schedule stands for the two:
+ *   schedule 0: linear (pkvo_budgets above)
+ *   schedule 1: geometric: r_l = C * q^l with the linear pyramid's ratio
+ *               between top and bottom layer, q^(L-1) = 1/(2 beta - 1), and
+ *               C such that sum_l r_l = L * A  (A = avg - alpha)
+ *   schedule 2: uniform, r_l = A (what SnapKV-style selection uses)
+ * Integerisation as above: floor, then one unit each to the largest
+ * fractional parts (ties to the lower layer); k_out[l] = alpha + integer.
+ * "Parity unpinned" by the paper (no formula, no numbers).
+ * ---------------------------------------------------------------------- */
+int pkvo_budgets_schedule(int32_t L, int32_t avg, int32_t beta, int32_t alpha,
+                          int32_t schedule, int32_t *k_out) {
+  if (schedule == 0) return pkvo_budgets(L, avg, beta, alpha, k_out);
+  if (L < 1 || beta < 1 || alpha < 0 || avg < alpha || !k_out) return 1;
+  if (schedule != 1 && schedule != 2) return 1;
+  const int64_t A = (int64_t)avg - alpha;
+  if (schedule == 2 || L == 1 || beta == 1) {
+    for (int32_t l = 0; l < L; ++l) k_out[l] = avg;
+    return 0;
+  }
+  double *r = (double *)malloc(sizeof(double) * (size_t)L);
+  const double q = pow(1.0 / (2.0 * (double)beta - 1.0), 1.0 / (double)(L - 1));
+  double sum = 0.0;
+  for (int32_t l = 0; l < L; ++l) {
+    r[l] = pow(q, (double)l);
+    sum += r[l];
+  }
+  int64_t given = 0;
+  for (int32_t l = 0; l < L; ++l) {
+    r[l] = (double)L * (double)A * r[l] / sum;
+    k_out[l] = (int32_t)floor(r[l]);
+    given += k_out[l];
+    r[l] -= floor(r[l]); /* fractional part */
+  }
+  for (int64_t left = (int64_t)L * A - given; left > 0; --left) {
+    int32_t best = 0;
+    for (int32_t l = 1; l < L; ++l)
+      if (r[l] > r[best]) best = l;
+    k_out[best] += 1;
+    r[best] = -1.0;
+  }
+  for (int32_t l = 0; l < L; ++l) k_out[l] += alpha;
+  free(r);
   return 0;
 }
 
@@ -372,6 +425,51 @@ int pkvo_compress_layer_lse(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
   return compress_layer_impl(B, Hq, Hkv, d, N, alpha, k_l, pool, pool_w, Q_win,
                              K, V, seq_lens, lse, K_out, V_out, idx_out,
                              count_out, pooled_out);
+}
+
+/* ------------------------------------------------------------------------
+ * Attention recall rate (appendix, "Attention Recall Rate Experiment"): the
+ * share of a query's attention over all keys that falls on the keys kept.
+ * For one sequence of n tokens and one KV head with its G query heads:
+ *   recall = mean over the G*alpha window queries r of
+ *            sum_{i in kept, i <= p_r} A_ri ,   A = causal softmax as above
+ * (the attention over all visible keys sums to 1, so the ratio is the kept
+ * mass).  kept: `count` positions, any order, each < n.
+ * ---------------------------------------------------------------------- */
+int pkvo_attention_recall(int32_t G, int32_t alpha, int32_t d, int32_t n,
+                          const uint16_t *q, const uint16_t *k,
+                          const int32_t *kept, int32_t count, double *recall) {
+  if (G < 1 || alpha < 1 || d < 1 || n < alpha || !q || !k || !kept ||
+      count < 0 || !recall)
+    return 1;
+  const int32_t R = G * alpha;
+  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  double *l = (double *)malloc(sizeof(double) * (size_t)n);
+  double total = 0.0;
+  for (int32_t r = 0; r < R; ++r) {
+    const int32_t p = n - alpha + r % alpha;
+    double mx = -INFINITY, Z = 0.0, keptmass = 0.0;
+    for (int32_t i = 0; i <= p; ++i) {
+      double dot = 0.0;
+      for (int32_t c = 0; c < d; ++c)
+        dot += bf16_to_f64(q[(size_t)r * d + c]) *
+               bf16_to_f64(k[(size_t)i * d + c]);
+      l[i] = dot * inv_sqrt_d;
+      if (l[i] > mx) mx = l[i];
+    }
+    for (int32_t i = 0; i <= p; ++i) Z += exp(l[i] - mx);
+    for (int32_t j = 0; j < count; ++j) {
+      if (kept[j] < 0 || kept[j] >= n) {
+        free(l);
+        return 1;
+      }
+      if (kept[j] <= p) keptmass += exp(l[kept[j]] - mx) / Z;
+    }
+    total += keptmass;
+  }
+  *recall = total / (double)R;
+  free(l);
+  return 0;
 }
 
 /* ------------------------------------------------------------------------

@@ -47,6 +47,10 @@ def _load():
         lib.pkvo_compress_layer_lse.argtypes = [i32] * 9 + [p] * 10
         lib.pkvo_scatter_pages.argtypes = [i32] * 7 + [p] * 6
         lib.pkvo_scatter_pages.restype = ctypes.c_int
+        lib.pkvo_budgets_schedule.argtypes = [i32] * 5 + [p]
+        lib.pkvo_budgets_schedule.restype = ctypes.c_int
+        lib.pkvo_attention_recall.argtypes = [i32] * 4 + [p, p, p, i32, p]
+        lib.pkvo_attention_recall.restype = ctypes.c_int
         for f in (lib.pkvo_budgets, lib.pkvo_window_scores, lib.pkvo_window_scores_lse, lib.pkvo_pool,
                   lib.pkvo_topk, lib.pkvo_compress_layer, lib.pkvo_compress_layer_lse,
                   lib.pkvo_num_threads):
@@ -177,3 +181,27 @@ def scatter_pages(K_out: np.ndarray, V_out: np.ndarray, count: np.ndarray, table
     if rc != 0:
         raise ValueError(f"pkvo_scatter_pages: status {rc}")
     return Kp, Vp
+
+
+SCHEDULE_LINEAR, SCHEDULE_GEOMETRIC, SCHEDULE_UNIFORM = 0, 1, 2
+
+
+def budgets_schedule(L: int, avg_budget: int, beta: int, alpha: int, schedule: int) -> np.ndarray:
+    out = np.zeros(max(L, 1), dtype=np.int32)
+    rc = _load().pkvo_budgets_schedule(L, avg_budget, beta, alpha, schedule, _ptr(out))
+    if rc != 0:
+        raise ValueError("pkvo_budgets_schedule: invalid arguments")
+    return out[:L]
+
+
+def attention_recall(q, k, kept) -> float:
+    """q: [G, alpha, d] bf16, k: [n, d] bf16 (the sequence's valid keys), kept: positions -> recall in [0, 1]."""
+    qb, kb = _bits(q), _bits(k)
+    G, alpha, d = qb.shape
+    kept = np.ascontiguousarray(kept, dtype=np.int32)
+    out = ctypes.c_double(0.0)
+    rc = _load().pkvo_attention_recall(G, alpha, d, kb.shape[0], _ptr(qb), _ptr(kb), _ptr(kept), kept.shape[0],
+                                       ctypes.byref(out))
+    if rc != 0:
+        raise ValueError("pkvo_attention_recall: invalid arguments")
+    return float(out.value)

@@ -88,3 +88,39 @@ def test_golden_file_is_what_the_oracle_gives():
             L, avg, beta, alpha = (int(x) for x in head.split())
             want = [int(x) for x in tail.split()]
             assert list(pkv_oracle.budgets(L, avg, beta, alpha)) == want
+
+
+# ---- other allocation strategies (appendix "Allocation Strategies") -------------------------------------
+
+
+def test_geometric_schedule_ratio_sum_and_monotone():
+    for (L, avg, beta, alpha) in [(32, 128, 20, 8), (32, 2048, 20, 32), (80, 512, 14, 16), (4, 128, 20, 8), (2, 64, 5, 8)]:
+        k = pkv_oracle.budgets_schedule(L, avg, beta, alpha, pkv_oracle.SCHEDULE_GEOMETRIC).astype(np.int64)
+        assert k.sum() == L * avg
+        assert np.all(np.diff(k) <= 0) and np.all(k >= alpha)
+        r = (k - alpha).astype(float)
+        # top / bottom as in the linear pyramid: 1 / (2 beta - 1), up to the integer rounding of each end
+        lo, hi = (r[-1] - 1) / (r[0] + 1), (r[-1] + 1) / max(r[0] - 1, 1)
+        assert lo <= 1.0 / (2 * beta - 1) <= hi
+        # constant ratio between neighbouring layers wherever the values are large enough to show it
+        big = r[:-1] > 200
+        if big.sum() > 3:
+            ratios = r[1:][big] / r[:-1][big]
+            assert ratios.max() - ratios.min() < 0.02
+
+
+def test_geometric_schedule_is_more_bottom_heavy_than_linear():
+    L, avg, beta, alpha = 32, 128, 20, 8
+    lin = pkv_oracle.budgets(L, avg, beta, alpha)
+    geo = pkv_oracle.budgets_schedule(L, avg, beta, alpha, pkv_oracle.SCHEDULE_GEOMETRIC)
+    assert geo[0] > lin[0] and geo[L // 2] < lin[L // 2] and geo.sum() == lin.sum()
+
+
+def test_uniform_schedule_and_degenerate_cases():
+    assert pkv_oracle.budgets_schedule(7, 100, 20, 8, pkv_oracle.SCHEDULE_UNIFORM).tolist() == [100] * 7
+    assert pkv_oracle.budgets_schedule(7, 100, 1, 8, pkv_oracle.SCHEDULE_GEOMETRIC).tolist() == [100] * 7   # beta = 1
+    assert pkv_oracle.budgets_schedule(1, 100, 20, 8, pkv_oracle.SCHEDULE_GEOMETRIC).tolist() == [100]
+    np.testing.assert_array_equal(pkv_oracle.budgets_schedule(32, 128, 20, 8, pkv_oracle.SCHEDULE_LINEAR),
+                                  pkv_oracle.budgets(32, 128, 20, 8))
+    with pytest.raises(ValueError):
+        pkv_oracle.budgets_schedule(4, 100, 20, 8, 3)

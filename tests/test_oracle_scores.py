@@ -228,3 +228,41 @@ def test_layer_with_supplied_denominators_indexes_them_by_batch_head_row():
             np.testing.assert_allclose(out["pooled"][b, g, : N - alpha], sm, rtol=1e-14)
             want = np.sort(np.argsort(-sm, kind="stable")[: 16 - alpha])
             np.testing.assert_array_equal(out["idx"][b, g, : 16 - alpha], want)
+
+
+# ---- attention recall rate (appendix, "Attention Recall Rate Experiment") --------------------------------
+
+
+def test_recall_is_one_when_everything_is_kept_and_drops_with_the_kept_set():
+    torch.manual_seed(21)
+    G, alpha, n, d = 2, 4, 60, 64
+    q, k = _bf16(torch.randn(G, alpha, d)), _bf16(torch.randn(n, d))
+    assert abs(pkv_oracle.attention_recall(q, k, np.arange(n)) - 1.0) < 1e-12
+    r_half = pkv_oracle.attention_recall(q, k, np.arange(0, n, 2))
+    r_rest = pkv_oracle.attention_recall(q, k, np.arange(1, n, 2))
+    assert 0.0 < r_half < 1.0 and abs(r_half + r_rest - 1.0) < 1e-12          # a partition of the keys
+    assert pkv_oracle.attention_recall(q, k, np.array([], dtype=np.int32)) == 0.0
+
+
+def test_recall_of_the_window_alone_with_identical_keys():
+    # identical keys: query t spreads its attention evenly over its n-alpha+t+1 visible keys, of which t+1 lie in
+    # the window -> recall of "window only" = mean_t (t+1)/(n-alpha+t+1)
+    G, alpha, n, d = 3, 5, 40, 64
+    torch.manual_seed(22)
+    q = _bf16(torch.randn(G, alpha, d))
+    k = _bf16(torch.randn(1, d)).repeat(n, 1)
+    want = np.mean([(t + 1) / (n - alpha + t + 1) for t in range(alpha)])
+    got = pkv_oracle.attention_recall(q, k, np.arange(n - alpha, n))
+    assert abs(got - want) < 1e-12
+
+
+def test_recall_equals_window_mass_plus_scores_at_the_kept_prefix_positions():
+    # ties the metric to the selection scores: sum of s_mean over kept prefix keys = (1/G) sum_h sum_t kept mass
+    torch.manual_seed(23)
+    G, alpha, n, d = 4, 6, 150, 64
+    q, k = _bf16(torch.randn(G, alpha, d)), _bf16(torch.randn(n, d))
+    _, s_mean = pkv_oracle.window_scores(q, k)
+    kept_prefix = np.sort(np.random.default_rng(1).choice(n - alpha, size=30, replace=False))
+    kept = np.concatenate([kept_prefix, np.arange(n - alpha, n)])
+    want = (s_mean[kept_prefix].sum() + (alpha - s_mean.sum())) / alpha
+    assert abs(pkv_oracle.attention_recall(q, k, kept) - want) < 1e-12

@@ -88,6 +88,10 @@ def main():
     ap.add_argument("--page-size", type=int, default=0,
                     help="variant: kept rows written into per-layer page pools of this page size through random "
                          "block tables (pkv_compress_layers_paged); not the headline configuration")
+    ap.add_argument("--recall", action="store_true",
+                    help="also report the attention recall rate of the kept sets (mean over layers, sequences and "
+                         "KV heads) for the linear, geometric and uniform allocation of the same average budget, and "
+                         "the time of the recall kernel; outside the timed region")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -204,6 +208,23 @@ def main():
                      "measured_read_GBps": read_gbps, "frac_of_measured_read": achieved / read_gbps},
         "kernel_ms_per_step": sum_ms,
     }
+    if args.recall:
+        rec = {}
+        for name, sched in (("linear", binding.SCHEDULE_LINEAR), ("geometric", binding.SCHEDULE_GEOMETRIC),
+                            ("uniform", binding.SCHEDULE_UNIFORM)):
+            ks_s = binding.budgets_schedule(w.L, avg, w.beta, w.alpha, sched)
+            c = call if sched == binding.SCHEDULE_LINEAR else \
+                binding.LayersCall(Qs, Ks, Vs, ks_s, w.pool, w.pool_w, seq_lens=lens_dev, lse=lses)
+            c.run()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            r = binding.attention_recall(c)
+            e1.record()
+            torch.cuda.synchronize()
+            rec[name] = float(torch.stack(r).mean())
+            rec.setdefault("kernel_ms", e0.elapsed_time(e1))
+            del c
+        out["attention_recall"] = rec
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, ks, layers_host, lens)
     print(json.dumps(out))

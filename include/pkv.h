@@ -76,6 +76,28 @@ int pkv_budgets(int32_t L, int32_t avg_budget, int32_t beta, int32_t alpha,
                 int32_t* k_out);
 
 /*
+ * Other allocation strategies of the paper's ablation (appendix "Allocation
+ * Strategies", which names a geometric and an exponential decay beside the
+ * linear one without a formula; written in the layer index both are
+ * r_l = C * q^l, so one schedule stands for the two).
+ *   PKV_SCHEDULE_LINEAR     pkv_budgets
+ *   PKV_SCHEDULE_GEOMETRIC  r_l = C * q^l over A = avg_budget - alpha, with the
+ *                           linear pyramid's ratio of top to bottom layer,
+ *                           q^(L-1) = 1/(2 beta - 1), and sum_l r_l = L*A
+ *   PKV_SCHEDULE_UNIFORM    k_out[l] = avg_budget (SnapKV-style selection)
+ * Integerisation, k_out, ownership and errors as pkv_budgets; an unknown
+ * schedule -> PKV_ERR_INVALID_ARG.
+ */
+typedef enum {
+  PKV_SCHEDULE_LINEAR = 0,
+  PKV_SCHEDULE_GEOMETRIC = 1,
+  PKV_SCHEDULE_UNIFORM = 2
+} pkv_schedule;
+
+int pkv_budgets_schedule(int32_t L, int32_t avg_budget, int32_t beta,
+                         int32_t alpha, int32_t schedule, int32_t* k_out);
+
+/*
  * Shape of one layer's compression problem.  Strides are in ELEMENTS (bf16);
  * the head dimension is always contiguous.
  */
@@ -149,7 +171,8 @@ size_t pkv_workspace_bytes(const pkv_layer_desc* desc, int32_t L);
  *            selection, defined for i < n_b-alpha when k_l < n_b; other
  *            entries are left untouched.
  * workspace  DEVICE, 256-byte aligned, >= pkv_workspace_bytes(desc, 1) bytes;
- *            contents on entry are irrelevant, contents on exit undefined.
+ *            contents on entry are irrelevant, contents on exit undefined
+ *            (except as pkv_attention_recall uses them).
  *            Concurrent calls must use distinct workspaces.
  * stream     hipStream_t.
  *
@@ -265,6 +288,29 @@ int pkv_compress_layers_paged(int32_t L, const pkv_layer_desc* descs,
                               int32_t* const* count_out,
                               float* const* scores_out, void* workspace,
                               size_t workspace_bytes, void* stream);
+
+/*
+ * Attention recall rate of the kept sets (appendix, "Attention Recall Rate
+ * Experiment"): the share of the window queries' attention over all keys
+ * that falls on the kept keys, averaged over the G*alpha window queries of
+ * a KV head: 1 - (window score mass on the dropped prefix keys) / alpha.
+ *
+ * Call it right after a pkv_compress_layers / _lse / _paged call, with the
+ * same L, descs, seq_lens and workspace, on the same stream and before
+ * anything else uses the workspace: it reads the un-pooled window scores
+ * that the call left there, and the call's idx_out.
+ *
+ * lse_supplied 1 if the call was given lse, else 0.
+ * idx_out      HOST array of L DEVICE pointers: the call's idx_out.
+ * recall_out   HOST array of L DEVICE pointers, each fp32 [B,Hkv], written:
+ *              1 for sequences that keep everything.
+ * Errors: as pkv_compress_layers for descs, pointers and workspace.
+ */
+int pkv_attention_recall(int32_t L, const pkv_layer_desc* descs,
+                         int32_t lse_supplied, const int32_t* seq_lens,
+                         const int32_t* const* idx_out,
+                         float* const* recall_out, const void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 /*
  * Measurement aid (no part of the method): pkv_compress_layers (lse NULL)

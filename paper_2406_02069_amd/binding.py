@@ -20,7 +20,8 @@ POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers",
-           "pkv_compress_layers_lse", "pkv_compress_layers_paged", "pkv_compress_layers_profiled", "pkv_probe_read", "pkv_status_string"]
+           "pkv_compress_layers_lse", "pkv_compress_layers_paged", "pkv_compress_layers_profiled",
+           "pkv_budgets_schedule", "pkv_attention_recall", "pkv_probe_read", "pkv_status_string"]
 
 
 class PkvError(RuntimeError):
@@ -64,6 +65,10 @@ def load() -> ctypes.CDLL:
         lib.pkv_compress_layers_paged.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 5 + \
             [ctypes.POINTER(PagedDesc)] + [vp] * 6 + [vp, ctypes.c_size_t, vp]
         lib.pkv_compress_layers_paged.restype = ctypes.c_int
+        lib.pkv_budgets_schedule.argtypes = [i32, i32, i32, i32, i32, vp]
+        lib.pkv_budgets_schedule.restype = ctypes.c_int
+        lib.pkv_attention_recall.argtypes = [i32, ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.pkv_attention_recall.restype = ctypes.c_int
         lib.pkv_status_string.argtypes = [ctypes.c_int]
         lib.pkv_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -81,6 +86,18 @@ def budgets(L: int, avg_budget: int, beta: int, alpha: int) -> List[int]:
     if rc != OK:
         raise PkvError(rc, "pkv_budgets")
     return [int(x) for x in out[:L]]
+
+
+SCHEDULE_LINEAR, SCHEDULE_GEOMETRIC, SCHEDULE_UNIFORM = 0, 1, 2
+
+
+def budgets_schedule(L: int, avg_budget: int, beta: int, alpha: int, schedule: int) -> List[int]:
+    """pkv_budgets_schedule: linear (pkv_budgets), geometric or uniform per-layer budgets."""
+    out = (ctypes.c_int32 * max(L, 1))()
+    rc = load().pkv_budgets_schedule(L, avg_budget, beta, alpha, schedule, out)
+    if rc != OK:
+        raise PkvError(rc, "pkv_budgets_schedule")
+    return [int(out[l]) for l in range(L)]
 
 
 def _check_bf16(t: torch.Tensor, name: str):
@@ -224,6 +241,19 @@ class LayersCall:
         if rc != OK:
             raise PkvError(rc, "pkv_compress_layers_lse" if self._lse is not None else "pkv_compress_layers")
         return self.outputs
+
+
+def attention_recall(call: "LayersCall") -> List[torch.Tensor]:
+    """pkv_attention_recall right after call.run(): per layer fp32 [B, Hkv]."""
+    B, Hkv = call.inputs[1][0].shape[0], call.inputs[1][0].shape[1]
+    outs = [torch.empty(B, Hkv, dtype=torch.float32, device=call.device) for _ in range(call.L)]
+    arr = ctypes.c_void_p * call.L
+    rc = load().pkv_attention_recall(call.L, call.descs, 1 if call._lse is not None else 0, call._args[3],
+                                     call._args[6], arr(*[t.data_ptr() for t in outs]), _p(call.workspace),
+                                     call.workspace.numel(), _stream_ptr(call.device))
+    if rc != OK:
+        raise PkvError(rc, "pkv_attention_recall")
+    return outs
 
 
 def compress_layers(Q_win, K, V, k_ls, pool, pool_w, seq_lens=None, want_scores=False):

@@ -431,6 +431,86 @@ int pkv_compress_layers_paged(int32_t L, const pkv_layer_desc* descs, const void
                               workspace, workspace_bytes, stream, nullptr, lse, lse != nullptr, paged, block_tables);
 }
 
+int pkv_budgets_schedule(int32_t L, int32_t avg_budget, int32_t beta, int32_t alpha, int32_t schedule,
+                         int32_t* k_out) {
+  if (schedule == PKV_SCHEDULE_LINEAR) return pkv_budgets(L, avg_budget, beta, alpha, k_out);
+  if (L < 1 || beta < 1 || alpha < 0 || avg_budget < alpha || !k_out) return PKV_ERR_INVALID_ARG;
+  if (schedule != PKV_SCHEDULE_GEOMETRIC && schedule != PKV_SCHEDULE_UNIFORM) return PKV_ERR_INVALID_ARG;
+  if (schedule == PKV_SCHEDULE_UNIFORM || L == 1 || beta == 1) {
+    for (int32_t l = 0; l < L; ++l) k_out[l] = avg_budget;
+    return PKV_OK;
+  }
+  // r_l = C q^l, q^(L-1) = 1 / (2 beta - 1) (the linear pyramid's ratio of top to bottom layer), sum_l r_l = L A
+  const double A = (double)(avg_budget - alpha);
+  const double q = pow(1.0 / (2.0 * (double)beta - 1.0), 1.0 / (double)(L - 1));
+  double frac[kMaxLayers];
+  if (L > kMaxLayers) return PKV_ERR_INVALID_ARG;
+  double sum = 0.0;
+  for (int32_t l = 0; l < L; ++l) {
+    frac[l] = pow(q, (double)l);
+    sum += frac[l];
+  }
+  int64_t given = 0;
+  for (int32_t l = 0; l < L; ++l) {
+    const double r = (double)L * A * frac[l] / sum;
+    k_out[l] = (int32_t)floor(r);
+    given += k_out[l];
+    frac[l] = r - floor(r);
+  }
+  // the missing units go, one each, to the largest fractional parts; equal parts: the lower layer first
+  for (int64_t left = (int64_t)L * (avg_budget - alpha) - given; left > 0; --left) {
+    int32_t best = 0;
+    for (int32_t l = 1; l < L; ++l)
+      if (frac[l] > frac[best]) best = l;
+    k_out[best] += 1;
+    frac[best] = -1.0;
+  }
+  for (int32_t l = 0; l < L; ++l) k_out[l] += alpha;
+  return PKV_OK;
+}
+
+int pkv_attention_recall(int32_t L, const pkv_layer_desc* descs, int32_t lse_supplied, const int32_t* seq_lens,
+                         const int32_t* const* idx_out, float* const* recall_out, const void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (L < 1 || L > kMaxLayers || !descs || !idx_out || !recall_out) return PKV_ERR_INVALID_ARG;
+  if ((uintptr_t)seq_lens & 3) return PKV_ERR_INVALID_ARG;
+  for (int32_t l = 0; l < L; ++l) {
+    const int rc = check_desc(&descs[l]);
+    if (rc != PKV_OK) return rc;
+    const pkv_layer_desc &a = descs[0], &b = descs[l];
+    if (a.B != b.B || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.N != b.N || a.alpha != b.alpha)
+      return PKV_ERR_INVALID_ARG;
+    if (!idx_out[l] || !recall_out[l] || ((uintptr_t)idx_out[l] & 3) || ((uintptr_t)recall_out[l] & 3))
+      return PKV_ERR_INVALID_ARG;
+  }
+  const pkv_layer_desc& d = descs[0];
+  const Plan plan = make_plan(d, L);
+  const int wrc = check_workspace(plan, workspace, workspace_bytes);
+  if (wrc != PKV_OK) return wrc;
+  // where the compress call left the un-pooled scores: one array per layer (resident path, already divided by the
+  // group size) or one partial per row block (streaming path)
+  const bool resident = use_resident(plan, lse_supplied != 0);
+  const int nrb = resident ? 1 : plan.nrb;
+  const float* raw = reinterpret_cast<const float*>(static_cast<const char*>(workspace) + plan.off_raw);
+  for (int32_t l0 = 0; l0 < L; l0 += kBatchMaxLayers) {
+    const int32_t nl = L - l0 < kBatchMaxLayers ? L - l0 : kBatchMaxLayers;
+    RecallArgs ra;
+    memset(&ra, 0, sizeof(ra));
+    for (int32_t i = 0; i < nl; ++i) {
+      ra.layer[i].idx = idx_out[l0 + i];
+      ra.layer[i].recall = recall_out[l0 + i];
+      ra.layer[i].k_l = descs[l0 + i].k_l;
+      ra.layer[i].k_cap = descs[l0 + i].k_l < d.N ? descs[l0 + i].k_l : d.N;
+    }
+    ra.raw = raw + (size_t)l0 * nrb * plan.BH * d.N;
+    ra.seq_lens = seq_lens;
+    ra.B = d.B; ra.Hkv = d.Hkv; ra.N = d.N; ra.alpha = d.alpha; ra.nrb = nrb;
+    ra.inv_G = resident ? 1.0f : 1.0f / (float)plan.G;
+    if (launch_recall(ra, nl, static_cast<hipStream_t>(stream)) != hipSuccess) return PKV_ERR_HIP;
+  }
+  return PKV_OK;
+}
+
 int pkv_compress_layers_profiled(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
                                  const void* const* K, const void* const* V, const float* const* lse,
                                  const int32_t* seq_lens, const pkv_paged_desc* paged,

@@ -138,7 +138,23 @@ struct GatherBatchArgs {
   int64_t kv_sb, kv_sh, kv_st;
 };
 
+// ---- attention recall of the kept set, from the un-pooled scores a compress call left in its workspace ----
+struct RecallLayer {
+  const int32_t* idx;  // [BH][k_cap] kept positions of the layer
+  float* recall;       // [BH]
+  int32_t k_l, k_cap;
+};
+
+struct RecallArgs {
+  RecallLayer layer[kBatchMaxLayers];
+  const float* raw;    // [L][nrb][BH][N], first layer of this launch
+  const int32_t* seq_lens;
+  int32_t B, Hkv, N, alpha, nrb;
+  float inv_G;         // factor applied to the sum of the partials
+};
+
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s);
+hipError_t launch_recall(const RecallArgs& a, int nlayers, hipStream_t s);
 hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipStream_t s);
 hipError_t launch_gather_batch(const GatherBatchArgs& a, hipStream_t s);
 hipError_t launch_probe_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s);

@@ -468,4 +468,54 @@ hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipSt
   return hipGetLastError();
 }
 
+// ---- attention recall rate (appendix, "Attention Recall Rate Experiment") ----
+// The attention of a window query over all keys it sees sums to 1, so the share that falls on the kept keys is
+// 1 - (mass on the dropped prefix keys); averaged over the G * alpha queries of a KV head that is
+//   recall = 1 - (sum_{i < n-alpha} s_i - sum_{kept prefix i} s_i) / alpha
+// with the un-pooled group-mean window scores s_i (the window keys are always kept).  One workgroup per
+// (layer, sequence, KV head): one coalesced pass over the scores, one gather over the kept positions.
+namespace {
+__global__ __launch_bounds__(256) void recall_kernel(const RecallArgs a) {
+  const RecallLayer& ly = a.layer[blockIdx.y];
+  const int bg = blockIdx.x;
+  const int b = bg / a.Hkv;
+  const int BH = a.B * a.Hkv;
+  int n = a.N;
+  if (a.seq_lens) {
+    n = a.seq_lens[b];
+    n = n < 0 ? 0 : (n > a.N ? a.N : n);
+  }
+  __shared__ float red[2][256];
+  float all = 0.f, kept = 0.f;
+  if (ly.k_l < n) {
+    const int npre = n - a.alpha, kk = ly.k_l - a.alpha;
+    for (int p = 0; p < a.nrb; ++p) {
+      const float* row = a.raw + (((size_t)blockIdx.y * a.nrb + p) * BH + bg) * a.N;
+      for (int i = threadIdx.x; i < npre; i += 256) all += row[i];
+      for (int j = threadIdx.x; j < kk; j += 256) {
+        const int i = ly.idx[(size_t)bg * ly.k_cap + j];
+        if ((uint32_t)i < (uint32_t)npre) kept += row[i];
+      }
+    }
+  }
+  red[0][threadIdx.x] = all;
+  red[1][threadIdx.x] = kept;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) {
+      red[0][threadIdx.x] += red[0][threadIdx.x + s];
+      red[1][threadIdx.x] += red[1][threadIdx.x + s];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0)
+    ly.recall[bg] = (ly.k_l < n) ? 1.f - (red[0][0] - red[1][0]) * a.inv_G / (float)a.alpha : 1.f;
+}
+}  // namespace
+
+hipError_t launch_recall(const RecallArgs& a, int nlayers, hipStream_t s) {
+  hipLaunchKernelGGL(recall_kernel, dim3(a.B * a.Hkv, nlayers), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 }  // namespace pkv

@@ -166,3 +166,28 @@ def test_compress_layers_paged_rejects_inconsistent_paging():
     assert call(binding.PagedDesc(16, 64, 8, 0), tables=None) == I      # no tables
     assert call(binding.PagedDesc(16, 64, 8, 0), tables=(ctypes.c_void_p * 2)(0x1000, 0x2002)) == I
     assert call(binding.PagedDesc(16, 64, 8, 0)) == binding.ERR_WORKSPACE   # valid so far
+
+
+def test_budget_schedules_equal_oracle_on_a_grid():
+    for sched in (pkv_oracle.SCHEDULE_LINEAR, pkv_oracle.SCHEDULE_GEOMETRIC, pkv_oracle.SCHEDULE_UNIFORM):
+        for L in (1, 2, 3, 4, 7, 28, 32, 40, 80, 126):
+            for avg in (64, 96, 128, 256, 512, 2048, 777):
+                for beta in (1, 2, 5, 14, 20):
+                    for alpha in (0, 8, 32):
+                        if avg < alpha:
+                            continue
+                        want = pkv_oracle.budgets_schedule(L, avg, beta, alpha, sched).tolist()
+                        assert binding.budgets_schedule(L, avg, beta, alpha, sched) == want, (sched, L, avg, beta, alpha)
+    with pytest.raises(binding.PkvError):
+        binding.budgets_schedule(4, 128, 20, 8, 9)
+
+
+def test_attention_recall_rejects_bad_arguments():
+    lib = binding.load()
+    descs = (binding.LayerDesc * 2)(_desc(), _desc())
+    arr = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    I = binding.ERR_INVALID_ARG
+    assert lib.pkv_attention_recall(2, descs, 0, None, None, arr, 0x10000, 1 << 30, None) == I
+    assert lib.pkv_attention_recall(2, descs, 0, None, arr, (ctypes.c_void_p * 2)(0x1000, None), 0x10000, 1 << 30, None) == I
+    assert lib.pkv_attention_recall(0, descs, 0, None, arr, arr, 0x10000, 1 << 30, None) == I
+    assert lib.pkv_attention_recall(2, descs, 0, None, arr, arr, 0x10000, 16, None) == binding.ERR_WORKSPACE

@@ -21,7 +21,9 @@
  * hand-written pool image and the identity table; for the attention recall:
  * everything kept gives 1, identical keys give a harmonic closed form, and
  * the kept mass equals the sum of the window scores at the kept positions;
- * for the geometric schedule: its defining ratios and sum.  The integer rounding of the budgets,
+ * for the geometric schedule: its defining ratios and sum; for the decoding
+ * attention over the compacted cache: a library softmax attention, the mean
+ * of V for identical keys and the single-key case.  The integer rounding of the budgets,
  * the pool padding rule and the GQA mean are conventions the paper does not
  * fix ("parity unpinned" by the paper; pinned only to the stated reading).
  *
@@ -512,6 +514,57 @@ int pkvo_scatter_pages(int32_t B, int32_t Hkv, int32_t d, int32_t k_cap,
         memcpy(K_pages + dst, K_out + src, sizeof(uint16_t) * (size_t)d);
         memcpy(V_pages + dst, V_out + src, sizeof(uint16_t) * (size_t)d);
       }
+  return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * The step after the path: one decoding query per sequence attends over the
+ * compacted cache of a layer (Sec. 3: after compression the model attends
+ * over K_s, V_s only; the kept rows carry the rotary phases of their original
+ * positions, so nothing is re-rotated).  For sequence b, query head h of KV
+ * head g = h / G and the count_b kept rows:
+ *   out[b][h] = sum_j softmax_j(q_bh . K_s[b][g][j] / sqrt(d)) V_s[b][g][j]
+ *   lse[b][h] = ln sum_j exp(q_bh . K_s[b][g][j] / sqrt(d))   (may be NULL)
+ * count_b = 0 gives a zero row and lse = -inf.
+ *   q : [B][Hq][d] bf16;  K_s, V_s : [B][Hkv][k_cap][d] bf16;  out: fp64.
+ * ---------------------------------------------------------------------- */
+int pkvo_decode_attention(int32_t B, int32_t Hq, int32_t Hkv, int32_t d,
+                          int32_t k_cap, const uint16_t *q,
+                          const uint16_t *Ks, const uint16_t *Vs,
+                          const int32_t *count, double *out, double *lse) {
+  if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv || d < 1 || k_cap < 1 || !q ||
+      !Ks || !Vs || !count || !out)
+    return 1;
+  const int32_t G = Hq / Hkv;
+  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  for (int32_t b = 0; b < B; ++b)
+    if (count[b] < 0 || count[b] > k_cap) return 1;
+  for (int32_t b = 0; b < B; ++b)
+    for (int32_t h = 0; h < Hq; ++h) {
+      const int32_t g = h / G, n = count[b];
+      const uint16_t *qr = q + ((size_t)b * Hq + h) * d;
+      const uint16_t *Kg = Ks + ((size_t)b * Hkv + g) * (size_t)k_cap * d;
+      const uint16_t *Vg = Vs + ((size_t)b * Hkv + g) * (size_t)k_cap * d;
+      double *o = out + ((size_t)b * Hq + h) * d;
+      double *l = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+      double mx = -INFINITY, Z = 0.0;
+      for (int32_t j = 0; j < n; ++j) {
+        double dot = 0.0;
+        for (int32_t c = 0; c < d; ++c)
+          dot += bf16_to_f64(qr[c]) * bf16_to_f64(Kg[(size_t)j * d + c]);
+        l[j] = dot * inv_sqrt_d;
+        if (l[j] > mx) mx = l[j];
+      }
+      for (int32_t j = 0; j < n; ++j) Z += exp(l[j] - mx);
+      for (int32_t c = 0; c < d; ++c) o[c] = 0.0;
+      for (int32_t j = 0; j < n; ++j) {
+        const double p = exp(l[j] - mx) / Z;
+        for (int32_t c = 0; c < d; ++c)
+          o[c] += p * bf16_to_f64(Vg[(size_t)j * d + c]);
+      }
+      if (lse) lse[(size_t)b * Hq + h] = n > 0 ? mx + log(Z) : -INFINITY;
+      free(l);
+    }
   return 0;
 }
 

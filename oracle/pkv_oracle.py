@@ -47,6 +47,8 @@ def _load():
         lib.pkvo_compress_layer_lse.argtypes = [i32] * 9 + [p] * 10
         lib.pkvo_scatter_pages.argtypes = [i32] * 7 + [p] * 6
         lib.pkvo_scatter_pages.restype = ctypes.c_int
+        lib.pkvo_decode_attention.argtypes = [i32] * 5 + [p] * 6
+        lib.pkvo_decode_attention.restype = ctypes.c_int
         lib.pkvo_budgets_schedule.argtypes = [i32] * 5 + [p]
         lib.pkvo_budgets_schedule.restype = ctypes.c_int
         lib.pkvo_attention_recall.argtypes = [i32] * 4 + [p, p, p, i32, p]
@@ -205,3 +207,19 @@ def attention_recall(q, k, kept) -> float:
     if rc != 0:
         raise ValueError("pkvo_attention_recall: invalid arguments")
     return float(out.value)
+
+
+def decode_attention(q, Ks, Vs, count):
+    """q [B,Hq,d], Ks, Vs [B,Hkv,k_cap,d] bf16 (torch) or uint16 bits, count [B] -> (out [B,Hq,d], lse [B,Hq]) fp64."""
+    qb, kb, vb = _bits(q), _bits(Ks), _bits(Vs)
+    B, Hq, d = qb.shape
+    _, Hkv, k_cap, _ = kb.shape
+    assert kb.shape == vb.shape == (B, Hkv, k_cap, d)
+    count = np.ascontiguousarray(count, dtype=np.int32)
+    out = np.zeros((B, Hq, d), dtype=np.float64)
+    lse = np.zeros((B, Hq), dtype=np.float64)
+    rc = _load().pkvo_decode_attention(B, Hq, Hkv, d, k_cap, _ptr(qb), _ptr(kb), _ptr(vb), _ptr(count), _ptr(out),
+                                       _ptr(lse))
+    if rc != 0:
+        raise ValueError("pkvo_decode_attention: invalid arguments")
+    return out, lse

@@ -92,6 +92,9 @@ def main():
                     help="also report the attention recall rate of the kept sets (mean over layers, sequences and "
                          "KV heads) for the linear, geometric and uniform allocation of the same average budget, and "
                          "the time of the recall kernel; outside the timed region")
+    ap.add_argument("--decode", action="store_true",
+                    help="also time the step after the path: one decoding query per sequence attending over every "
+                         "layer's compacted cache (pkv_decode_attention, one launch per layer); outside the timed region")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -208,6 +211,37 @@ def main():
                      "measured_read_GBps": read_gbps, "frac_of_measured_read": achieved / read_gbps},
         "kernel_ms_per_step": sum_ms,
     }
+    if args.decode:
+        outs = call.run()
+        torch.cuda.synchronize()
+        gq = torch.Generator(device=dev).manual_seed(99)
+        qd = [torch.randn(w.B, w.Hq, w.d, generator=gq, device=dev).to(torch.bfloat16) for _ in range(w.L)]
+        o_buf = torch.empty(w.B, w.Hq, w.d, dtype=torch.float32, device=dev)
+        d_ws = torch.empty(64 << 20, dtype=torch.uint8, device=dev)   # ample for any shape here
+
+        def decode_step():
+            for l in range(w.L):
+                if paged is not None:
+                    binding.decode_attention(qd[l], outs[l][0], outs[l][1], outs[l][3], block_table=paged[2][l],
+                                             k_cap=min(ks[l], w.N), out=o_buf, workspace=d_ws)
+                else:
+                    binding.decode_attention(qd[l], outs[l][0], outs[l][1], outs[l][3], out=o_buf, workspace=d_ws)
+
+        for _ in range(20):
+            decode_step()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            decode_step()
+        e1.record()
+        torch.cuda.synchronize()
+        dms = e0.elapsed_time(e1) / args.steps
+        rows = sum(int(o[3].clamp(min=0).sum()) for o in outs)          # kept rows over all layers and sequences
+        dbytes = rows * w.Hkv * w.d * 2 * 2 + w.L * w.B * w.Hq * w.d * (2 + 4)
+        out["decode_attention"] = {"ms_per_step": dms, "launches": w.L, "us_per_launch": dms * 1e3 / w.L,
+                                   "algorithmic_bytes_per_step": dbytes,
+                                   "achieved_GBps": dbytes / (dms * 1e-3) / 1e9,
+                                   "frac_of_hbm_peak": dbytes / (dms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
     if args.recall:
         rec = {}
         for name, sched in (("linear", binding.SCHEDULE_LINEAR), ("geometric", binding.SCHEDULE_GEOMETRIC),

@@ -313,6 +313,65 @@ int pkv_attention_recall(int32_t L, const pkv_layer_desc* descs,
                          size_t workspace_bytes, void* stream);
 
 /*
+ * The step after the path: decoding attention of one new query per sequence
+ * over a layer's compacted cache (Sec. 3: after compression the model attends
+ * over the kept keys and values only).  The kept rows carry the rotary phases
+ * of their original positions, so q is taken as given (rotated at its own
+ * position by the caller) and nothing is re-rotated.
+ *   out[b][h] = sum_{j < count_b} softmax_j(q_bh . K_bgj / sqrt(d)) V_bgj,
+ *   g = h / (Hq/Hkv);  fp32 accumulation and output.
+ * The cache is what pkv_compress_layer(s) wrote (page_size 0: compact
+ * [B,Hkv,k_cap,d] with strides c_*) or what pkv_compress_layers_paged wrote
+ * (page_size > 0: pool [num_pages,Hkv,page_size,d] with this layer's block
+ * table; a page number out of range makes its rows count as absent).
+ */
+typedef struct {
+  int32_t B, Hq, Hkv; /* Hq % Hkv == 0, Hq/Hkv <= 8                          */
+  int32_t d;          /* 64 or 128                                           */
+  int32_t k_cap;      /* rows per sequence the cache can hold, <= 4096       */
+  int32_t page_size;  /* 0: compact cache; > 0: paged                        */
+  int32_t num_pages;  /* paged: pages in the pool                            */
+  int32_t max_pages;  /* paged: entries per sequence in the block table,
+                         >= ceil(k_cap / page_size)                          */
+  int32_t reserved;   /* must be 0                                           */
+  int32_t reserved2;  /* padding, ignored                                    */
+  int64_t c_sb, c_sh, c_st; /* compact: element strides of K_cache/V_cache   */
+} pkv_decode_desc;
+
+/*
+ * Bytes of DEVICE workspace pkv_decode_attention needs for this shape (0 for
+ * shapes it serves with one workgroup per sequence and head; 0 as well if
+ * the descriptor is invalid).  HOST only, pure.
+ */
+size_t pkv_decode_workspace_bytes(const pkv_decode_desc* desc);
+
+/*
+ * desc        HOST.
+ * q           DEVICE bf16 [B,Hq,d] contiguous, 16-byte aligned.
+ * K_cache, V_cache  DEVICE bf16, layouts above, 16-byte aligned.
+ * block_table DEVICE int32 [B,max_pages] (paged) or NULL (compact).
+ * count       DEVICE int32 [B]: valid rows per sequence (count_out of the
+ *             compression call); values outside [0, k_cap] are clamped, so
+ *             the error codes -1 / -2 read as an empty cache.
+ * out         DEVICE fp32 [B,Hq,d] contiguous, written (zero rows for an
+ *             empty cache).
+ * lse_out     DEVICE fp32 [B,Hq] or NULL: natural log of the softmax
+ *             denominator (-inf for an empty cache).
+ * workspace   DEVICE, 256-byte aligned, >= pkv_decode_workspace_bytes(desc)
+ *             bytes (may be NULL when that is 0); contents irrelevant on
+ *             entry, undefined on exit; concurrent calls need distinct ones.
+ * stream      hipStream_t.  Asynchronous, never allocates.
+ * Errors: PKV_ERR_INVALID_ARG (NULL / misaligned pointers, shape or stride
+ * rules violated), PKV_ERR_UNSUPPORTED (d, Hq/Hkv > 8, k_cap > 4096),
+ * PKV_ERR_WORKSPACE, PKV_ERR_HIP.
+ */
+int pkv_decode_attention(const pkv_decode_desc* desc, const void* q,
+                         const void* K_cache, const void* V_cache,
+                         const int32_t* block_table, const int32_t* count,
+                         float* out, float* lse_out, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid (no part of the method): pkv_compress_layers (lse NULL)
  * or pkv_compress_layers_lse (lse given), compact (paged NULL) or paged
  * output (paged and block_tables given; K_out / V_out are then the page

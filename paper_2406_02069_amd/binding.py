@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers",
            "pkv_compress_layers_lse", "pkv_compress_layers_paged", "pkv_compress_layers_profiled",
-           "pkv_budgets_schedule", "pkv_attention_recall", "pkv_probe_read", "pkv_status_string"]
+           "pkv_budgets_schedule", "pkv_attention_recall", "pkv_decode_attention", "pkv_decode_workspace_bytes", "pkv_probe_read", "pkv_status_string"]
 
 
 class PkvError(RuntimeError):
@@ -35,6 +35,12 @@ class LayerDesc(ctypes.Structure):
                 ("B", "Hq", "Hkv", "d", "N", "alpha", "k_l", "pool", "pool_w", "reserved")] + \
                [(n, ctypes.c_int64) for n in
                 ("q_sb", "q_sh", "q_st", "kv_sb", "kv_sh", "kv_st", "o_sb", "o_sh", "o_st")]
+
+
+class DecodeDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hq", "Hkv", "d", "k_cap", "page_size", "num_pages", "max_pages",
+                                              "reserved", "reserved2")] + \
+               [(n, ctypes.c_int64) for n in ("c_sb", "c_sh", "c_st")]
 
 
 class PagedDesc(ctypes.Structure):
@@ -69,6 +75,10 @@ def load() -> ctypes.CDLL:
         lib.pkv_budgets_schedule.restype = ctypes.c_int
         lib.pkv_attention_recall.argtypes = [i32, ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.pkv_attention_recall.restype = ctypes.c_int
+        lib.pkv_decode_attention.argtypes = [ctypes.POINTER(DecodeDesc)] + [vp] * 8 + [ctypes.c_size_t, vp]
+        lib.pkv_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
+        lib.pkv_decode_workspace_bytes.restype = ctypes.c_size_t
+        lib.pkv_decode_attention.restype = ctypes.c_int
         lib.pkv_status_string.argtypes = [ctypes.c_int]
         lib.pkv_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -254,6 +264,40 @@ def attention_recall(call: "LayersCall") -> List[torch.Tensor]:
     if rc != OK:
         raise PkvError(rc, "pkv_attention_recall")
     return outs
+
+
+def decode_attention(q: torch.Tensor, K_cache: torch.Tensor, V_cache: torch.Tensor, count: torch.Tensor,
+                     block_table: Optional[torch.Tensor] = None, k_cap: Optional[int] = None, want_lse: bool = False,
+                     out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None):
+    """pkv_decode_attention.  q bf16 [B,Hq,d]; compact cache: K_cache, V_cache bf16 [B,Hkv,k_cap,d] (any row strides);
+    paged cache: pools [num_pages,Hkv,page_size,d], block_table int32 [B,max_pages] and k_cap given.
+    Returns (out fp32 [B,Hq,d], lse fp32 [B,Hq] or None)."""
+    assert q.dtype == torch.bfloat16 and q.dim() == 3 and q.is_contiguous() and count.dtype == torch.int32
+    assert K_cache.dtype == torch.bfloat16 and V_cache.dtype == torch.bfloat16
+    B, Hq, d = q.shape
+    if block_table is None:
+        Hkv, k_cap = K_cache.shape[1], K_cache.shape[2]
+        assert K_cache.stride() == V_cache.stride() and K_cache.stride(3) == 1
+        desc = DecodeDesc(B, Hq, Hkv, d, k_cap, 0, 0, 0, 0, 0, K_cache.stride(0), K_cache.stride(1), K_cache.stride(2))
+    else:
+        num_pages, Hkv, page_size, _ = K_cache.shape
+        assert K_cache.is_contiguous() and V_cache.is_contiguous() and block_table.is_contiguous()
+        assert block_table.dtype == torch.int32 and k_cap is not None
+        desc = DecodeDesc(B, Hq, Hkv, d, k_cap, page_size, num_pages, block_table.shape[1], 0, 0, 0, 0, 0)
+    if out is None:
+        out = torch.empty(B, Hq, d, dtype=torch.float32, device=q.device)
+    if want_lse and lse is None:
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
+    need = load().pkv_decode_workspace_bytes(ctypes.byref(desc))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    rc = load().pkv_decode_attention(ctypes.byref(desc), q.data_ptr(), K_cache.data_ptr(), V_cache.data_ptr(),
+                                     _p(block_table), count.data_ptr(), out.data_ptr(), _p(lse), _p(workspace),
+                                     0 if workspace is None else workspace.numel(), _stream_ptr(q.device))
+    if rc != OK:
+        raise PkvError(rc, "pkv_decode_attention")
+    return out, lse
 
 
 def compress_layers(Q_win, K, V, k_ls, pool, pool_w, seq_lens=None, want_scores=False):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libpkv.so")
-SOURCES = ["pkv_api.hip", "pkv_score.hip", "pkv_resident.hip", "pkv_select.hip", "pkv_gather.hip"]
+SOURCES = ["pkv_api.hip", "pkv_score.hip", "pkv_resident.hip", "pkv_select.hip", "pkv_gather.hip", "pkv_decode.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -431,6 +431,64 @@ int pkv_compress_layers_paged(int32_t L, const pkv_layer_desc* descs, const void
                               workspace, workspace_bytes, stream, nullptr, lse, lse != nullptr, paged, block_tables);
 }
 
+static int check_decode_desc(const pkv_decode_desc* desc) {
+  if (!desc) return PKV_ERR_INVALID_ARG;
+  const pkv_decode_desc& d = *desc;
+  if (d.B < 1 || d.Hq < 1 || d.Hkv < 1 || d.Hq % d.Hkv != 0 || d.k_cap < 1 || d.reserved != 0) return PKV_ERR_INVALID_ARG;
+  if (d.page_size < 0) return PKV_ERR_INVALID_ARG;
+  if (d.page_size > 0) {
+    if (d.num_pages < 1 || d.max_pages < ((int64_t)d.k_cap + d.page_size - 1) / d.page_size) return PKV_ERR_INVALID_ARG;
+  } else {
+    const int64_t st[3] = {d.c_sb, d.c_sh, d.c_st};
+    for (int i = 0; i < 3; ++i)
+      if (st[i] < 0 || st[i] % 8 != 0) return PKV_ERR_INVALID_ARG;
+    if (d.c_st < d.d) return PKV_ERR_INVALID_ARG;
+  }
+  if (d.d != 64 && d.d != 128) return PKV_ERR_UNSUPPORTED;
+  if (d.Hq / d.Hkv > 8 || d.k_cap > kDecodeMaxRows || d.B > 65535) return PKV_ERR_UNSUPPORTED;
+  return PKV_OK;
+}
+
+size_t pkv_decode_workspace_bytes(const pkv_decode_desc* desc) {
+  if (check_decode_desc(desc) != PKV_OK) return 0;
+  const int S = decode_splits(desc->B, desc->Hkv, desc->k_cap);
+  if (S == 1) return 0;
+  return (size_t)desc->B * desc->Hkv * S * (8 * (size_t)desc->d + 16) * sizeof(float);
+}
+
+int pkv_decode_attention(const pkv_decode_desc* desc, const void* q, const void* K_cache, const void* V_cache,
+                         const int32_t* block_table, const int32_t* count, float* out, float* lse_out,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  if (!desc || !q || !K_cache || !V_cache || !count || !out) return PKV_ERR_INVALID_ARG;
+  const int drc = check_decode_desc(desc);
+  if (drc != PKV_OK) return drc;
+  const pkv_decode_desc& d = *desc;
+  if (!aligned16(q) || !aligned16(K_cache) || !aligned16(V_cache) || ((uintptr_t)count & 3) || ((uintptr_t)out & 3) ||
+      ((uintptr_t)lse_out & 3) || ((uintptr_t)block_table & 3))
+    return PKV_ERR_INVALID_ARG;
+  if (d.page_size > 0 && !block_table) return PKV_ERR_INVALID_ARG;
+  const size_t need = pkv_decode_workspace_bytes(desc);
+  if (need > 0 && (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)) return PKV_ERR_WORKSPACE;
+  DecodeArgs da;
+  memset(&da, 0, sizeof(da));
+  da.S = decode_splits(d.B, d.Hkv, d.k_cap);
+  da.chunk = ((d.k_cap + da.S - 1) / da.S + 31) / 32 * 32;
+  da.part_o = static_cast<float*>(workspace);
+  da.part_mz = da.part_o ? da.part_o + (size_t)d.B * d.Hkv * da.S * 8 * d.d : nullptr;
+  da.q = static_cast<const uint16_t*>(q);
+  da.K = static_cast<const uint16_t*>(K_cache);
+  da.V = static_cast<const uint16_t*>(V_cache);
+  da.table = block_table;
+  da.count = count;
+  da.out = out;
+  da.lse = lse_out;
+  da.B = d.B; da.Hq = d.Hq; da.Hkv = d.Hkv; da.G = d.Hq / d.Hkv; da.d = d.d; da.k_cap = d.k_cap;
+  da.page_size = d.page_size; da.num_pages = d.num_pages; da.max_pages = d.max_pages;
+  da.c_sb = d.c_sb; da.c_sh = d.c_sh; da.c_st = d.c_st;
+  da.scale_log2 = (float)(1.4426950408889634 / sqrt((double)d.d));
+  return launch_decode_attention(da, static_cast<hipStream_t>(stream)) == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
 int pkv_budgets_schedule(int32_t L, int32_t avg_budget, int32_t beta, int32_t alpha, int32_t schedule,
                          int32_t* k_out) {
   if (schedule == PKV_SCHEDULE_LINEAR) return pkv_budgets(L, avg_budget, beta, alpha, k_out);

@@ -153,6 +153,26 @@ struct RecallArgs {
   float inv_G;         // factor applied to the sum of the partials
 };
 
+// ---- decoding attention over a compacted (possibly paged) cache ----
+constexpr int kDecodeMaxRows = 4096;  // kept rows per sequence the LDS probability table can hold
+struct DecodeArgs {
+  const uint16_t* q;     // [B][Hq][d]
+  const uint16_t* K;     // compact [B][Hkv][k_cap][d] (strides c_*) or pool [num_pages][Hkv][page_size][d]
+  const uint16_t* V;
+  const int32_t* table;  // [B][max_pages], paged only
+  const int32_t* count;  // [B]
+  float* out;            // [B][Hq][d]
+  float* lse;            // [B][Hq] or null
+  float* part_o;         // [B][Hkv][S][8][d] un-normalised partial outputs (S > 1)
+  float* part_mz;        // [B][Hkv][S][8][2] reference exponent and sum of the partial result
+  int32_t B, Hq, Hkv, G, d, k_cap, page_size, num_pages, max_pages;
+  int32_t S, chunk;      // key ranges per (sequence, head); keys per range (multiple of 32)
+  int64_t c_sb, c_sh, c_st;
+  float scale_log2;      // log2(e) / sqrt(d)
+};
+int decode_splits(int B, int Hkv, int k_cap);
+hipError_t launch_decode_attention(const DecodeArgs& a, hipStream_t s);
+
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s);
 hipError_t launch_recall(const RecallArgs& a, int nlayers, hipStream_t s);
 hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipStream_t s);

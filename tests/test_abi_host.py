@@ -191,3 +191,30 @@ def test_attention_recall_rejects_bad_arguments():
     assert lib.pkv_attention_recall(2, descs, 0, None, arr, (ctypes.c_void_p * 2)(0x1000, None), 0x10000, 1 << 30, None) == I
     assert lib.pkv_attention_recall(0, descs, 0, None, arr, arr, 0x10000, 1 << 30, None) == I
     assert lib.pkv_attention_recall(2, descs, 0, None, arr, arr, 0x10000, 16, None) == binding.ERR_WORKSPACE
+
+
+def test_decode_attention_rejects_bad_arguments():
+    lib = binding.load()
+    I, U = binding.ERR_INVALID_ARG, binding.ERR_UNSUPPORTED
+
+    def desc(**kw):
+        base = dict(B=2, Hq=32, Hkv=8, d=128, k_cap=128, page_size=0, num_pages=0, max_pages=0, reserved=0, reserved2=0,
+                    c_sb=8 * 128 * 128, c_sh=128 * 128, c_st=128)
+        base.update(kw)
+        return binding.DecodeDesc(**base)
+
+    def call(d, q=0x1000, K=0x2000, V=0x3000, tb=None, cnt=0x4000, out=0x5000):
+        return lib.pkv_decode_attention(ctypes.byref(d), q, K, V, tb, cnt, out, None, 0x10000, 1 << 30, None)
+
+    assert call(desc(), q=None) == I and call(desc(), cnt=None) == I and call(desc(), out=None) == I
+    assert call(desc(), K=0x2004) == I                                 # misaligned cache
+    assert call(desc(Hq=30)) == I and call(desc(k_cap=0)) == I and call(desc(reserved=3)) == I
+    assert call(desc(c_st=64)) == I and call(desc(c_sh=12)) == I        # rows overlap / not 16-byte aligned
+    assert call(desc(page_size=16, num_pages=64, max_pages=8)) == I    # paged without a table
+    assert call(desc(page_size=16, num_pages=64, max_pages=7), tb=0x6000) == I   # table too short for k_cap
+    assert call(desc(d=96)) == U and call(desc(Hq=128)) == U and call(desc(k_cap=5000)) == U
+    big = desc(k_cap=2048)                                              # small batch, long cache: split over key ranges
+    need = lib.pkv_decode_workspace_bytes(ctypes.byref(big))
+    assert need == 2 * 8 * 8 * (8 * 128 + 16) * 4 and lib.pkv_decode_workspace_bytes(ctypes.byref(desc(B=64))) == 0
+    assert lib.pkv_decode_attention(ctypes.byref(big), 0x1000, 0x2000, 0x3000, None, 0x4000, 0x5000, None, 0x10000,
+                                    need - 1, None) == binding.ERR_WORKSPACE

@@ -39,6 +39,12 @@
 // Every wait is bounded: a workgroup that spins too long raises the error word and carries on, so the
 // grid always drains.  The launch uses exactly 512 workgroups, two per compute unit (register- and
 // LDS-limited), which the host checks against the device before choosing this path.
+//
+// One-sweep variant (second template argument): when the caller supplies the softmax denominators of the
+// window queries (the log-sum-exp its attention kernel computed during prefill), steps 2 and 3 fall away
+// and the kernel is step 4 alone over a stream of keys: no workgroup waits for another, the (unit, part)
+// items are handed out from a counter, and the next item's keys, Q block and denominators travel while the
+// current item is computed.  Bound by HBM instead of the vector pipe.
 #include <type_traits>
 
 #include "pkv_internal.h"

@@ -116,3 +116,13 @@ def test_bad_page_number_is_reported_and_never_written_through():
     gKp = bits(Kp)
     assert (gKp[[5, 6]] == SENTINEL).all()                                # pages no table names: untouched
     assert (gKp[[0, 1, 2, 3, 4, 7]] != SENTINEL).any(axis=(1, 2, 3)).all()  # the named ones were written
+
+
+def test_more_layers_than_one_launch_holds():
+    # 45 layers: the gather runs in two launches (40 layers per kernel-argument table), each with its own tables
+    alpha = 4
+    Q, K, V = _rand(2, 4, 2, 64, 400, alpha, seed=12)
+    L = 45
+    Qs = [Q.roll(l, dims=2).contiguous() for l in range(L)]
+    ks = [alpha + 3 + (11 * l) % 70 for l in range(L)]
+    _run_paged(Qs, [K] * L, [V] * L, ks, alpha, synth.POOL_MAX, 3, 8, seed=6)

@@ -223,6 +223,43 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       uint32_t U = (uint32_t)npre, G = 0;
       uint32_t* list = lkeys;  // the un-pooled scores are no longer needed
       int bit = 31;
+      {
+        // The leading bits that all keys share (sign, the top of the exponent: scores span a few binades) are T's
+        // leading bits as well (count(key >= that prefix) = npre >= kk, and nothing lies above it): they are
+        // read off the largest and the smallest key instead of being searched, one round of counting each.
+        uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+          if (j < nval) {
+            kmax = max(kmax, rkeys[j]);
+            kmin = min(kmin, rkeys[j]);
+          }
+        }
+#pragma unroll
+        for (int sft = 32; sft > 0; sft >>= 1) {
+          kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, sft));
+          kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, sft));
+        }
+        if (lane == 0) {
+          scan32[wave] = kmax;
+          scan32[NW + wave] = kmin;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          kmax = max(kmax, scan32[w]);
+          kmin = min(kmin, scan32[NW + w]);
+        }
+        __syncthreads();  // the slots are reused by the rounds below
+        const uint32_t diff = kmax ^ kmin;
+        if (diff == 0u) {  // all keys equal: T is that key
+          prefix = kmax;
+          bit = -1;
+        } else {
+          bit = 31 - __clz((int)diff);                      // the first bit in which keys differ
+          prefix = (bit == 31) ? 0u : (kmax >> (bit + 1)) << (bit + 1);
+        }
+      }
       // rounds over all keys, until few enough are open
       constexpr int kList = 512;  // open keys that the finishing wave can hold (8 per lane)
       for (; bit >= 0 && U > (uint32_t)kList; --bit) {

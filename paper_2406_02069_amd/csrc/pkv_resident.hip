@@ -212,14 +212,28 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   // One unit as this workgroup sees it (all fields wave-uniform).
   struct Unit {
     int u, n, npre, nparts;
+    int j;  // position of the unit in the list of the group pair (two-sweep path)
     const uint16_t* Q;
     const uint16_t* K;
     const float* lse;  // the unit's G * alpha denominators (row r = head * alpha + t), LSE only
     int wkey0;         // first key of this wave in the unit, LSE only (there the part changes from unit to unit)
   };
-  // First unit at or after `u` (in steps of nslots) in which this workgroup has keys to score.
-  auto find_unit = [&](int u, Unit& d) {
-    for (; u < a.U; u += nslots) {
+  // Which units a group works on.  The units are dealt round-robin to the pairs of groups that share compute units
+  // (first and second workgroup of every unit of an XCD cluster), and a pair's list is split between its two
+  // groups in the ratio (32 - w) : w.  The second workgroup of a compute unit gets the issue slots the first one
+  // leaves, so its group needs about a tenth longer per unit; with equal shares the first groups would sit idle
+  // at the end.  (Only speed depends on the split; w = 16 alternates.)
+  const bool paired = a.ngroups >= 2;
+  const int npairs = paired ? nslots / 2 : nslots;
+  const int pair_slot = paired ? (group >> 1) * a.UPG + sub : slot_id;
+  auto mine = [&](int j) { return !paired || ((((j + 1) * a.set1_w) >> 5) != ((j * a.set1_w) >> 5)) == ((group & 1) != 0); };
+  // First unit at or after position j of the pair's list that is this group's and in which this workgroup has
+  // keys to score.
+  auto find_unit = [&](int j, Unit& d) {
+    for (;; ++j) {
+      const int u = pair_slot + j * npairs;
+      if (u >= a.U) break;
+      if (!mine(j)) continue;
       const int l = u / BH;
       const int bg = u - l * BH;
       const int b = bg / a.Hkv;
@@ -232,6 +246,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       if (a.layer[l].k_l >= n) continue;  // whole sequence kept: no scores needed (uniform over the unit)
       if (key0 >= n) continue;            // no keys here; this part is not counted at the barrier
       d.u = u;
+      d.j = j;
       d.n = n;
       d.npre = n - a.alpha;
       d.nparts = (n + kResidentKeys - 1) / kResidentKeys;
@@ -399,7 +414,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     take((int)blockIdx.x, cur_u);
     if (cur_u.u < a.U) take(kResidentGrid + (int)blockIdx.x, nxt_u);
   } else {
-    find_unit(slot_id, cur_u);
+    find_unit(0, cur_u);
   }
   if (cur_u.u >= a.U) return;
   int buf = 0;
@@ -430,7 +445,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
 
   while (cur_u.u < a.U) {
     const int u = cur_u.u, n = cur_u.n, npre = cur_u.npre, nparts = cur_u.nparts;
-    if constexpr (!LSE) find_unit(u + nslots, nxt_u);
+    if constexpr (!LSE) find_unit(cur_u.j + 1, nxt_u);
     const bool has_next = nxt_u.u < a.U;
     const int wkey = LSE ? cur_u.wkey0 : wkey0;
     const bool has_keys = wkey < n;                       // wave-uniform

@@ -28,8 +28,10 @@
  *    needed in production): PKV_SCORE_PATH=stream forces the per-layer
  *    scoring kernels that read K twice instead of the register-resident one;
  *    PKV_STAGGER=<ticks of 10 ns> sets the start offset between workgroup
- *    groups of the resident kernel; PKV_SPIN_LIMIT=<probes> bounds its
- *    waits (0: give up at once, which a test uses to see count_out = -1).
+ *    groups of the resident kernel; PKV_SET1_W=<1..31> the share (of 32)
+ *    of the units that the groups of second workgroups take;
+ *    PKV_SPIN_LIMIT=<probes> bounds its waits (0: give up at once, which a
+ *    test uses to see count_out = -1).
  */
 #ifndef PKV_H_
 #define PKV_H_

@@ -30,6 +30,8 @@
  *    PKV_STAGGER=<ticks of 10 ns> sets the start offset between workgroup
  *    groups of the resident kernel; PKV_SET1_W=<1..31> the share (of 32)
  *    of the units that the groups of second workgroups take;
+ *    PKV_FOLD=counter keeps the arrival counter in the exchange of softmax
+ *    statistics where the tagged exchange would be used;
  *    PKV_SPIN_LIMIT=<probes> bounds its waits (0: give up at once, which a
  *    test uses to see count_out = -1).
  */

@@ -221,6 +221,11 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       ra.stagger = resident_stagger(lse_mode ? 0 : 250);
       ra.spin_limit = resident_spin_limit();
       ra.set1_w = resident_set1_weight();
+      // every part of a group takes part in every unit when all sequences have the full length; worth it when a
+      // unit has enough parts to spread the rows over (test hook: PKV_FOLD=counter keeps the arrival counter)
+      const char* fold = getenv("PKV_FOLD");
+      ra.tagged = (!lse_mode && seq_lens == nullptr && plan.TPU >= 16 && !(fold && !strcmp(fold, "counter"))) ? 1 : 0;
+      ra.part_words = (int32_t)((size_t)plan.ngroups * plan.UPG * plan.TPU * plan.res_Rpad * 2);
       ra.d = d.d;
       ra.q_sb = d.q_sb; ra.q_sh = d.q_sh; ra.q_st = d.q_st;
       ra.kv_sb = d.kv_sb; ra.kv_sh = d.kv_sh; ra.kv_st = d.kv_st;

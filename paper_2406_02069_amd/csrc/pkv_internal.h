@@ -88,6 +88,8 @@ struct ResidentArgs {
   int32_t L, B, Hq, Hkv, G, alpha, N, R, Rpad, nrb, TPU, U, d;
   int32_t ngroups;  // independent groups of workgroups: 512 / group size
   int32_t UPG;      // units a group works on at the same time: group size / TPU
+  int32_t tagged;   // 1: statistics words carry a phase bit, parts fold their own rows (no arrival counter)
+  int32_t part_words;  // 32-bit words of the per-part statistics (zeroed before a tagged launch)
   int32_t set1_w;   // share (of 32) of a group pair's units that goes to the group of second workgroups
   int32_t stagger;  // start offset between consecutive groups, in 10 ns ticks
   int32_t lse_mode;    // 1: every layer carries lse; one sweep, no exchange between workgroups

@@ -24,6 +24,9 @@
 //   3. arrives at the unit's counter.  The last part to arrive folds all parts into the per-row
 //      normaliser c_r = max + log2(sum) and publishes it, tagged with the unit number; the others poll
 //      the tagged words.  (Agent-scope relaxed atomics: written through, never served from a stale line.)
+//      When every part takes part in every unit (no ragged batch) there is no counter: the statistics
+//      words carry a phase bit, and part p folds the rows p, p + nparts, ... as soon as their words show
+//      it.
 //   4. sweep 2: same products from the same registers, s_i = sum_r exp2(kappa q_r.k_i - c_r), written
 //      once per key (already divided by the group size).
 //
@@ -410,6 +413,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   if (tid == 0) qsmem[SEG] = u32x4{0u, 0u, 0u, 0u};  // pad slot of row 0: never written by the staging
   Unit cur_u, nxt_u;
   int drawn = 0;  // LSE: the counter's value at this unit's draw (the item is 1024 + that)
+  int seqpos = 0; // units this workgroup has worked on (two-sweep path, tagged mode: all parts of a group agree)
   if constexpr (LSE) {
     take((int)blockIdx.x, cur_u);
     if (cur_u.u < a.U) take(kResidentGrid + (int)blockIdx.x, nxt_u);
@@ -447,6 +451,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     const int u = cur_u.u, n = cur_u.n, npre = cur_u.npre, nparts = cur_u.nparts;
     if constexpr (!LSE) find_unit(cur_u.j + 1, nxt_u);
     const bool has_next = nxt_u.u < a.U;
+    const uint32_t phase = (uint32_t)(seqpos & 1) ^ 1u;  // tagged mode: the bit this unit's statistics carry
+    ++seqpos;
     const int wkey = LSE ? cur_u.wkey0 : wkey0;
     const bool has_keys = wkey < n;                       // wave-uniform
     // tile t needs masks iff it reaches beyond the prefix (causal window, end of the sequence)
@@ -638,22 +644,58 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
           merge_stats(m, z, stat[w][0][tid].x, stat[w][0][tid].y);
           merge_stats(m, z, stat[w][1][tid].x, stat[w][1][tid].y);
         }
-        // device-scope store: written through, so that other XCDs see it without an L2 write-back
-        st64(reinterpret_cast<u64*>(part + rb * kRowBlock + tid), ((u64)__float_as_uint(z) << 32) | __float_as_uint(m));
+        // device-scope store: written through, so that other XCDs see it without an L2 write-back.  Tagged mode:
+        // the sign bit of the sum (never negative) carries the unit's phase bit, so the word announces itself.
+        uint32_t zb = __float_as_uint(z);
+        if (a.tagged) zb = (zb & 0x7FFFFFFFu) | (phase << 31);
+        st64(reinterpret_cast<u64*>(part + rb * kRowBlock + tid), ((u64)zb << 32) | __float_as_uint(m));
       }
     }
-    __syncthreads();  // also waits for the stores above to be acknowledged
+    if (a.tagged) lds_barrier();  // (nobody waits for these stores: their readers look at the tag)
+    else __syncthreads();         // also waits for the stores above to be acknowledged
     PKV_T(1);
     PKV_TN(2);
 
     // ---- arrive; the last part folds all parts into the per-row normaliser and publishes it ----
+    // Tagged mode (every part takes part in every unit of its group): no counter and no last arriver.  Part p folds
+    // the rows p, p + nparts, ..., one wave per row and one lane per part: a lane probes its part's word of the row
+    // until it shows this unit's phase bit.  Two hops of the exchange fall away (the acknowledgement of the
+    // statistics stores and the round trip of the arrival counter).
     const unsigned tag = (unsigned)u + 1u;
-    if (tid == 0) {
-      const int prev = __hip_atomic_fetch_add(&a.cnt[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_last = (prev == nparts - 1);
+    bool last = false;
+    if (a.tagged) {
+      for (int r = part_id + wave * nparts; r < a.R; r += kWaves * nparts) {
+        float m = -INFINITY, z = 0.f;
+        for (int p = lane; p < nparts; p += 64) {
+          const u64* src = reinterpret_cast<const u64*>(part_base + (size_t)p * a.Rpad + r);
+          int spins = 0;
+          u64 w;
+          for (;;) {
+            w = ld64(src);
+            if ((uint32_t)(w >> 63) == phase) break;
+            __builtin_amdgcn_s_sleep(2);
+            if (++spins > a.spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+              __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              break;
+            }
+          }
+          merge_stats(m, z, __uint_as_float((uint32_t)w), __uint_as_float((uint32_t)(w >> 32) & 0x7FFFFFFFu));
+        }
+#pragma unroll
+        for (int s = 32; s > 0; s >>= 1) {
+          const float m2 = __shfl_xor(m, s), z2 = __shfl_xor(z, s);
+          merge_stats(m, z, m2, z2);
+        }
+        if (lane == 0) st64(&cbuf[r], ((u64)tag << 32) | __float_as_uint(-(m + fast_log2(z)) * a.inv_kappa));
+      }
+    } else {
+      if (tid == 0) {
+        const int prev = __hip_atomic_fetch_add(&a.cnt[u], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (prev == nparts - 1);
+      }
+      __syncthreads();
+      last = s_last != 0;
     }
-    __syncthreads();
-    const bool last = s_last != 0;
     if (last) {
 #ifdef PKV_RES_TIMING
       tstamp[3] -= wall_clock64();
@@ -921,9 +963,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
 #endif
 }
 
-__global__ void zero_kernel(int32_t* p, int n) {
+__global__ void zero_kernel(int32_t* p, int n, int32_t* p2, int n2) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
+  else if (i - n < n2) p2[i - n] = 0;
 }
 
 }  // namespace
@@ -946,8 +989,10 @@ static hipError_t launch_resident(const ResidentArgs& a, hipStream_t s) {
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s) {
   // the counters, the error word and the tagged normaliser words must start at zero (with supplied denominators
   // only the error word is looked at, by the selection kernel)
-  const int nz = a.sync_words;
-  hipLaunchKernelGGL(zero_kernel, dim3((nz + 255) / 256), dim3(256), 0, s, a.zero_base, nz);
+  // (tagged mode: the per-part statistics as well, whose words carry a phase bit)
+  const int nz = a.sync_words, nz2 = a.tagged ? a.part_words : 0;
+  hipLaunchKernelGGL(zero_kernel, dim3((nz + nz2 + 255) / 256), dim3(256), 0, s, a.zero_base, nz,
+                     reinterpret_cast<int32_t*>(a.part), nz2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.lse_mode) {

@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: the 32k config)")
     ap.add_argument("--avg-budget", type=int, default=None)
+    ap.add_argument("--seq-len", type=int, default=None,
+                    help="variant: the same workload at another context length (e.g. 131072); no cpu_baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lse", action="store_true",
                     help="variant: one-sweep scoring with the window queries' softmax denominators supplied "
@@ -106,6 +108,10 @@ def main():
 
     dev = "cuda:0"
     w = synth.WORKLOADS[args.config]
+    if args.seq_len is not None and args.seq_len != w.N:
+        w = w.scaled(name=f"{w.name}@N{args.seq_len}", N=args.seq_len)
+    else:
+        args.seq_len = None
     avg = args.avg_budget or w.avg_budgets[0]
     ks = binding.budgets(w.L, avg, w.beta, w.alpha)
     lens = synth.seq_lens(w)
@@ -113,7 +119,7 @@ def main():
     lens_dev = None if lens is None else torch.from_numpy(lens).to(dev)
 
     # all layers resident in HBM; a bounded set of layers is also kept on the host for the oracle
-    if args.lse or args.page_size > 0:
+    if args.lse or args.page_size > 0 or args.seq_len is not None:
         args.no_cpu_baseline = True
     n_host = 0 if args.no_cpu_baseline else min(w.L, 32)
     host_ids = sorted(set([0, w.L - 1] + list(range(1, w.L - 1))[: max(n_host - 2, 0)])) if n_host else []
@@ -187,7 +193,8 @@ def main():
     out = {
         "metric": "compressed prefill tokens/sec (all layers, select+gather); achieved HBM GB/s" +
                   (" [variant: softmax denominators supplied, one sweep]" if args.lse else "") +
-                  (f" [variant: paged output, page size {args.page_size}]" if args.page_size > 0 else ""),
+                  (f" [variant: paged output, page size {args.page_size}]" if args.page_size > 0 else "") +
+                  (f" [variant: context length {args.seq_len}]" if args.seq_len is not None else ""),
         "value": sum_n / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1,

@@ -6,13 +6,15 @@
 //   A. pooled[i] = pool_w-wide max / average of the un-pooled scores, prefix only.  When the prefix fits in
 //      LDS (<= 32768 keys) all loads are issued at once, the scores are pooled out of LDS into registers
 //      (32 positions per thread, each wave owning a contiguous range of 2048 positions) and stay there; longer
-//      prefixes go tile by tile through LDS and keep their keys in the pooled array in global memory.  The
+//      prefixes go through LDS in tiles of 16384 positions (all loads of a tile in flight at once) and keep their
+//      keys in the pooled array in global memory.  The
 //      fp32 bit patterns are the selection keys (scores are >= 0, so unsigned order = numeric order).
 //   B. the kk-th largest key T.  Keys in registers: binary search on T, one bit per round from the top; a
 //      round counts the keys >= the candidate (per lane, then per wave through ballots, then 16 wave counts
 //      through LDS: one barrier, no atomics).  As soon as at most 512 keys still agree with the decided
 //      bits, those keys move to a list and one wave decides the remaining bits on its own.
-//      Keys in global memory: radix select, three digit levels (11 + 11 + 10 bits) with LDS histograms.
+//      Keys in global memory: radix select with LDS histograms, digits of up to 11 bits below the leading bits
+//      that all keys share (read off the largest and the smallest key).
 //   C. ordered emission: every wave owns a contiguous range of positions; ballots give each kept key
 //      its rank, so positions with key > T, and the lowest positions with key == T, come out in
 //      ascending order, followed by the window positions.
@@ -26,7 +28,7 @@ namespace {
 
 constexpr int NT = kSelectThreads;
 constexpr int NW = NT / 64;
-constexpr int TS = 2048;           // pooling tile (outputs per iteration)
+constexpr int TL = 16384;          // pooling tile of long prefixes (outputs per iteration)
 constexpr int HIST = 2048;         // bins of the widest digit
 constexpr int kLdsKeys = 32768;    // prefix lengths up to this keep their keys in LDS
 
@@ -61,13 +63,12 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* s
 template <bool LDSKEYS>
 __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb_stride, float inv_G, float* pooled,
                                             bool write_pooled, int32_t* idx, int npre, int kk, int alpha, int pool,
-                                            int pool_w, uint32_t* lkeys, float* tilebuf, uint32_t* hist,
+                                            int pool_w, uint32_t* lkeys, uint32_t* hist,
                                             uint32_t* scan32, uint32_t* sel, long long* g_dbg) {
   const int tid = threadIdx.x;
   PKV_ST(0);
   const int lane = tid & 63, wave = tid >> 6;
   const uint32_t* gkeys = reinterpret_cast<const uint32_t*>(pooled);
-  auto key_at = [&](int i) -> uint32_t { return LDSKEYS ? lkeys[i] : gkeys[i]; };
 
   // ---- A. group mean + pooling ----
   constexpr int PER = kLdsKeys / NT;   // positions per thread when the prefix lives in LDS
@@ -80,6 +81,7 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
   // number of the thread's positions that exist (position pos0 + 64 * j exists iff j < nval): one register instead
   // of 32 position registers kept alive for the comparisons
   const int nval = min(max((npre - pos0 + 63) >> 6, 0), kLdsKeys / NT);
+  uint32_t gmax = 0u, gmin = 0xFFFFFFFFu;  // long prefixes: largest and smallest key this thread has produced
   if (LDSKEYS) {
     // The whole prefix fits in LDS: every load of the un-pooled scores is in flight at once (one memory round
     // trip), then each thread pools its positions out of LDS; the pooled values stay in registers, already in
@@ -173,33 +175,42 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
     for (int j = 0; j < PER; ++j) rkeys[j] = (j < nval) ? __float_as_uint(v[j]) : 0u;
     PKV_ST(2);
   } else {
-    for (int t0 = 0; t0 < npre; t0 += TS) {
-      for (int e = tid; e < TS + 2 * r; e += NT) {
-        const int i = t0 - r + e;
-        float v = is_max ? -INFINITY : 0.f;
-        if (i >= 0 && i < npre) {
-          float s = 0.f;
-          for (int q = 0; q < nrb; ++q) s += raw[q * rb_stride + i];
-          v = s * inv_G;
+    // Long prefix: tiles of TL outputs go through LDS, every load of a tile in flight at once; the pooled values
+    // are the keys, kept in global memory.  On the way the largest and the smallest key are noted.
+    float* lsc = reinterpret_cast<float*>(lkeys);
+    constexpr int PT = TL / NT;  // outputs per thread and tile; one more load covers the 2 r halo positions
+    static_assert(TL + 2 * (kMaxPoolW / 2) <= (PT + 1) * NT && TL + 2 * (kMaxPoolW / 2) <= kLdsKeys, "tile fits");
+    for (int t0 = 0; t0 < npre; t0 += TL) {
+      float v[PT + 1];
+#pragma unroll
+      for (int j = 0; j <= PT; ++j) {
+        const int e = tid + NT * j, i = t0 - r + e;
+        v[j] = 0.f;
+        if (e < TL + 2 * r && i >= 0 && i < npre) {
+          v[j] = raw[i];
+          for (int q = 1; q < nrb; ++q) v[j] += raw[q * rb_stride + i];
         }
-        tilebuf[e] = v;
+      }
+#pragma unroll
+      for (int j = 0; j <= PT; ++j) {
+        const int e = tid + NT * j, i = t0 - r + e;
+        if (e < TL + 2 * r) lsc[e] = (i >= 0 && i < npre) ? v[j] * inv_G : (is_max ? -INFINITY : 0.f);
       }
       __syncthreads();
-      for (int e = tid; e < TS; e += NT) {
-        const int i = t0 + e;
+#pragma unroll
+      for (int j = 0; j < PT; ++j) {
+        const int e = tid + NT * j, i = t0 + e;
         if (i < npre) {
-          float v;
-          if (r == 0) {
-            v = tilebuf[e];
-          } else if (is_max) {
-            v = tilebuf[e];
-            for (int u = 1; u <= 2 * r; ++u) v = fmaxf(v, tilebuf[e + u]);
+          float acc = lsc[e];
+          if (is_max) {
+            for (int u = 1; u <= 2 * r; ++u) acc = fmaxf(acc, lsc[e + u]);
           } else {
-            v = 0.f;
-            for (int u = 0; u <= 2 * r; ++u) v += tilebuf[e + u];
-            v *= inv_w;
+            for (int u = 1; u <= 2 * r; ++u) acc += lsc[e + u];
+            if (r > 0) acc *= inv_w;
           }
-          pooled[i] = v;
+          pooled[i] = acc;
+          gmax = max(gmax, __float_as_uint(acc));
+          gmin = min(gmin, __float_as_uint(acc));
         }
       }
       __syncthreads();
@@ -322,40 +333,72 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
         prefix = sel[0];
       }
     } else {
-    uint32_t prefix_mask = 0;
-    const int shifts[3] = {21, 10, 0};
-    const int bits[3] = {11, 11, 10};
+      // Keys in global memory: radix select.  The leading bits that all keys share are T's as well and are read off
+      // the largest and the smallest key; below them digits of up to 11 bits, most significant first, each with an
+      // LDS histogram over the keys that agree with the digits decided so far.  (Starting at the first bit in which
+      // keys differ also spreads the first digit over many bins: scores span a few binades, and a digit made of
+      // sign and exponent bits would send nearly every key to the same few counters.)  Every thread has its 16
+      // loads of a round in flight before it counts.
 #pragma unroll
-    for (int lvl = 0; lvl < 3; ++lvl) {
-      const int shift = shifts[lvl];
-      const uint32_t dmask = (1u << bits[lvl]) - 1u;
-      for (int e = tid; e < HIST; e += NT) hist[e] = 0;
-      __syncthreads();
-      for (int i = tid; i < npre; i += NT) {
-        const uint32_t key = key_at(i);
-        if ((key & prefix_mask) == prefix) atomicAdd(&hist[(key >> shift) & dmask], 1u);
+      for (int sft = 32; sft > 0; sft >>= 1) {
+        gmax = max(gmax, (uint32_t)__shfl_xor((int)gmax, sft));
+        gmin = min(gmin, (uint32_t)__shfl_xor((int)gmin, sft));
+      }
+      if (lane == 0) {
+        scan32[wave] = gmax;
+        scan32[NW + wave] = gmin;
       }
       __syncthreads();
-      // thread t owns bins 2t, 2t+1; suffix sums over the bins owned by higher threads
-      const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
-      uint32_t total;
-      const uint32_t incl = block_inclusive_scan(h0 + h1, scan32, &total);
-      uint32_t above = total - incl;
-      if (above < remaining && above + h1 >= remaining) {
-        sel[0] = (uint32_t)(2 * tid + 1);
-        sel[1] = above;
-      }
-      above += h1;
-      if (above < remaining && above + h0 >= remaining) {
-        sel[0] = (uint32_t)(2 * tid);
-        sel[1] = above;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        gmax = max(gmax, scan32[w]);
+        gmin = min(gmin, scan32[NW + w]);
       }
       __syncthreads();
-      prefix |= sel[0] << shift;
-      prefix_mask |= dmask << shift;
-      remaining -= sel[1];
-      __syncthreads();
-    }
+      const uint32_t diff = gmax ^ gmin;
+      int top = (diff == 0u) ? 0 : 32 - __clz((int)diff);  // undecided low bits
+      prefix = (top >= 32) ? 0u : (gmax >> top) << top;
+      constexpr int NB = 16;  // keys per thread and round
+      while (top > 0) {
+        const int nb = min(11, top), shift = top - nb;
+        const uint32_t dmask = (1u << nb) - 1u;
+        for (int e = tid; e < HIST; e += NT) hist[e] = 0;
+        __syncthreads();
+        for (int i0 = 0; i0 < npre; i0 += NB * NT) {
+          uint32_t key[NB];
+#pragma unroll
+          for (int j = 0; j < NB; ++j) {
+            const int i = i0 + tid + NT * j;
+            key[j] = i < npre ? gkeys[i] : 0u;
+          }
+#pragma unroll
+          for (int j = 0; j < NB; ++j) {
+            const int i = i0 + tid + NT * j;
+            const bool open = top >= 32 || (key[j] >> top) == (prefix >> top);
+            if (i < npre && open) atomicAdd(&hist[(key[j] >> shift) & dmask], 1u);
+          }
+        }
+        __syncthreads();
+        // thread t owns bins 2t, 2t+1; suffix sums over the bins owned by higher threads
+        const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+        uint32_t total;
+        const uint32_t incl = block_inclusive_scan(h0 + h1, scan32, &total);
+        uint32_t above = total - incl;
+        if (above < remaining && above + h1 >= remaining) {
+          sel[0] = (uint32_t)(2 * tid + 1);
+          sel[1] = above;
+        }
+        above += h1;
+        if (above < remaining && above + h0 >= remaining) {
+          sel[0] = (uint32_t)(2 * tid);
+          sel[1] = above;
+        }
+        __syncthreads();
+        prefix |= sel[0] << shift;
+        remaining -= sel[1];
+        top = shift;
+        __syncthreads();
+      }
     }
     PKV_ST(3);
     const uint32_t T = prefix;           // bit pattern of the kk-th largest pooled score
@@ -409,40 +452,63 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
         eq_before += __popcll(beq);
       }
     } else {
-    const uint32_t need_eq = remaining;  // keys equal to T to take, lowest positions first (>= 1)
-    const int cw = ((npre + NW - 1) / NW + 63) & ~63;  // positions per wave, multiple of 64
-    const int w0 = min(wave * cw, npre), w1 = min(w0 + cw, npre);
-    uint32_t cgt = 0, ceq = 0;
-    for (int base = w0; base < w1; base += 64) {
-      const int i = base + lane;
-      const uint32_t key = i < w1 ? key_at(i) : 0u;
-      cgt += __popcll(__ballot(i < w1 && key > T));
-      ceq += __popcll(__ballot(i < w1 && key == T));
-    }
-    __syncthreads();
-    if (lane == 0) {
-      hist[wave] = cgt;
-      hist[NW + wave] = ceq;
-    }
-    __syncthreads();
-    uint32_t gt_before = 0, eq_before = 0;
-    for (int w = 0; w < wave; ++w) {
-      gt_before += hist[w];
-      eq_before += hist[NW + w];
-    }
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    for (int base = w0; base < w1; base += 64) {
-      const int i = base + lane;
-      const uint32_t key = i < w1 ? key_at(i) : 0u;
-      const bool gt = i < w1 && key > T, eq = i < w1 && key == T;
-      const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
-      const uint32_t gtb = gt_before + __popcll(bgt & lt_mask);
-      const uint32_t eqb = eq_before + __popcll(beq & lt_mask);
-      if (gt) idx[gtb + min(eqb, need_eq)] = i;
-      if (eq && eqb < need_eq) idx[gtb + eqb] = i;
-      gt_before += __popcll(bgt);
-      eq_before += __popcll(beq);
-    }
+      // every wave owns a contiguous range of positions; two passes over its keys (count, then emit), eight
+      // groups of 64 positions per round with their loads in flight together
+      constexpr int NE = 8;
+      const int cw = ((npre + NW - 1) / NW + 63) & ~63;  // positions per wave, multiple of 64
+      const int w0 = min(wave * cw, npre), w1 = min(w0 + cw, npre);
+      uint32_t cgt = 0, ceq = 0;
+      for (int base = w0; base < w1; base += 64 * NE) {
+        uint32_t key[NE];
+#pragma unroll
+        for (int j = 0; j < NE; ++j) {
+          const int i = base + 64 * j + lane;
+          key[j] = i < w1 ? gkeys[i] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < NE; ++j) {
+          const int i = base + 64 * j + lane;
+          cgt += __popcll(__ballot(i < w1 && key[j] > T));
+          ceq += __popcll(__ballot(i < w1 && key[j] == T));
+        }
+      }
+      __syncthreads();
+      if (lane == 0) {
+        hist[wave] = cgt;
+        hist[NW + wave] = ceq;
+      }
+      __syncthreads();
+      uint32_t gt_before = 0, eq_before = 0, gt_total = 0;
+      for (int w = 0; w < NW; ++w) {
+        gt_total += hist[w];
+        if (w < wave) {
+          gt_before += hist[w];
+          eq_before += hist[NW + w];
+        }
+      }
+      const uint32_t need_eq = (uint32_t)kk - gt_total;  // keys equal to T to take, lowest positions first (>= 1)
+      const unsigned long long lt_mask = (1ull << lane) - 1ull;
+      for (int base = w0; base < w1; base += 64 * NE) {
+        uint32_t key[NE];
+#pragma unroll
+        for (int j = 0; j < NE; ++j) {
+          const int i = base + 64 * j + lane;
+          key[j] = i < w1 ? gkeys[i] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < NE; ++j) {
+          const int i = base + 64 * j + lane;
+          const bool gt = i < w1 && key[j] > T, eq = i < w1 && key[j] == T;
+          const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+          if ((bgt | beq) == 0) continue;
+          const uint32_t gtb = gt_before + __popcll(bgt & lt_mask);
+          const uint32_t eqb = eq_before + __popcll(beq & lt_mask);
+          if (gt) idx[gtb + min(eqb, need_eq)] = i;
+          if (eq && eqb < need_eq) idx[gtb + eqb] = i;
+          gt_before += __popcll(bgt);
+          eq_before += __popcll(beq);
+        }
+      }
     }
   }
   for (int t = tid; t < alpha; t += NT) idx[kk + t] = npre + t;
@@ -451,7 +517,6 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
 
 __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatchArgs a) {
   extern __shared__ uint32_t lkeys[];  // kLdsKeys entries
-  __shared__ float tilebuf[TS + 2 * 32];
   __shared__ uint32_t hist[HIST];
   __shared__ uint32_t scan32[2 * NW];
   __shared__ uint32_t sel[2];
@@ -484,10 +549,10 @@ __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatch
   float* pooled = ly.pooled + (size_t)bg * a.N;
   if (npre <= kLdsKeys)
     select_unit<true>(raw, a.nrb, rb_stride, a.inv_G, pooled, ly.write_pooled != 0, idx, npre, kk, a.alpha, a.pool,
-                      a.pool_w, lkeys, tilebuf, hist, scan32, sel, a.dbg);
+                      a.pool_w, lkeys, hist, scan32, sel, a.dbg);
   else
     select_unit<false>(raw, a.nrb, rb_stride, a.inv_G, pooled, true, idx, npre, kk, a.alpha, a.pool, a.pool_w,
-                       lkeys, tilebuf, hist, scan32, sel, a.dbg);
+                       lkeys, hist, scan32, sel, a.dbg);
 }
 
 }  // namespace

@@ -81,6 +81,18 @@ def test_head_geometries(d, Hq, Hkv, alpha, score_path):
         _run_and_compare(_W(alpha, pool, pw), 0, alpha + 100, Q, K, V)
 
 
+def test_more_query_rows_per_kv_head_than_the_resident_kernels_hold():
+    # G * alpha = 16 * 64 = 1024 > 512: the per-layer streaming kernels take the call whatever path is asked for,
+    # eight 128-row blocks whose partial scores are added by the selection kernel
+    alpha, N = 64, 3000
+    Q, K, V = _rand(1, 32, 2, 128, N, alpha, seed=77)
+    lens = np.array([N], dtype=np.int32)
+    for pool, pw in ((synth.POOL_MAX, 7), (synth.POOL_AVG, 5)):
+        st, _ = _run_and_compare(_W(alpha, pool, pw), 0, alpha + 150, Q, K, V)
+        assert st["units"] == 2
+        _run_and_compare(_W(alpha, pool, pw), 0, alpha + 150, Q, K, V, lens)
+
+
 def test_edge_budgets_and_lengths(score_path):
     alpha = 8
     Q, K, V = _rand(3, 8, 2, 128, 300, alpha, seed=5)

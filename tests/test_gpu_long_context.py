@@ -81,3 +81,61 @@ def test_beyond_the_resident_limit_streams():
     out = binding.compress_layer(Qs[0], Ks[0], Vs[0], 500, synth.POOL_MAX, 7, want_scores=True)
     torch.cuda.synchronize()
     compare_layer(Qs[0], Ks[0], Vs[0], 500, ALPHA, synth.POOL_MAX, 7, None, out)
+
+
+def _small(N, alpha, seed, B=1, Hq=2, Hkv=2, d=64):
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    Q = torch.randn(B, Hq, alpha, d, generator=g, device=DEV).to(torch.bfloat16)
+    K = torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    return Q, K, V
+
+
+@pytest.mark.parametrize("pool,pw", [(synth.POOL_NONE, 1), (synth.POOL_MAX, 63), (synth.POOL_AVG, 9), (synth.POOL_MAX, 3)])
+def test_long_prefix_selection_edges(pool, pw):
+    # the selection of prefixes beyond 32768 keys: smallest and largest budgets, a pool as wide as a tile's halo
+    # allows, lengths around the tile size of the pooling (16384) and the per-wave ranges of the emission
+    alpha = 8
+    for N, k_ls in ((32768 + alpha + 1, (alpha + 1, 500)), (49152 + alpha, (alpha + 1, 49152 + alpha - 1)),
+                    (40001, (alpha, 3000, 40000, 40001))):
+        Q, K, V = _small(N, alpha, seed=N % 97 + pw)
+        for k_l in k_ls:
+            print("long selection", pool, pw, "N", N, "k_l", k_l, flush=True)
+            out = binding.compress_layer(Q, K, V, k_l, pool, pw, want_scores=True)
+            torch.cuda.synchronize()
+            compare_layer(Q, K, V, k_l, alpha, pool, pw, None, out)
+
+
+def test_long_prefix_with_equal_scores():
+    # identical keys: every prefix key gets the same score, the cut falls inside one plateau that spans the whole
+    # prefix, and the lowest positions win; then two plateaus (a block of keys that scores higher)
+    alpha, N = 8, 36000
+    Q, K, V = _small(N, alpha, seed=5)
+    K[:] = K[:, :, :1]
+    out = binding.compress_layer(Q, K, V, alpha + 1000, synth.POOL_NONE, 1, want_scores=True)
+    torch.cuda.synchronize()
+    compare_layer(Q, K, V, alpha + 1000, alpha, synth.POOL_NONE, 1, None, out)
+    assert out[2][0, 0, :1000].cpu().tolist() == list(range(1000))
+    K[:, :, 20000:20300] = (Q[:, :1, 3:4].float() * 0.5).to(torch.bfloat16)
+    out = binding.compress_layer(Q, K, V, alpha + 1000, synth.POOL_NONE, 1, want_scores=True)
+    torch.cuda.synchronize()
+    compare_layer(Q, K, V, alpha + 1000, alpha, synth.POOL_NONE, 1, None, out)
+
+
+def test_long_prefix_with_non_finite_scores_stays_in_bounds():
+    alpha, N, k_l = 8, 40000, 300
+    Q, K, V = _small(N, alpha, seed=6)
+    K[0, 0, 1234] = float("nan")
+    out = binding.compress_layer(Q, K, V, k_l, synth.POOL_MAX, 7, want_scores=True)
+    torch.cuda.synchronize()
+    idx = out[2].cpu().numpy()
+    assert out[3].cpu().tolist() == [k_l]
+    for g in range(2):
+        row = idx[0, g]
+        assert row.min() >= 0 and row.max() < N and np.all(np.diff(row) > 0), g
+        assert row[-alpha:].tolist() == list(range(N - alpha, N)), g
+    Kc = K.clone()
+    Kc[0, 0, 1234] = 0
+    ref = binding.compress_layer(Q, Kc, V, k_l, synth.POOL_MAX, 7, want_scores=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx[0, 1], ref[2][0, 1].cpu().numpy())   # the other head is unaffected

@@ -13,8 +13,9 @@
 //      next tile while the current one is multiplied.  The useful rows of the product are elements 0..3 of both
 //      wave halves.  Logits go to LDS (log2 domain).
 //   B. per head: maximum and sum over the range's keys; 2^(x - max) stored in place.
-//   C. values: a wave moves one value row per load (each lane its d/64 columns), eight rows in flight; every lane
-//      keeps G x d/64 partial outputs, added up over the waves through LDS in a fixed order.
+//   C. values: a lane moves 16 bytes of a value row per load (a wave: 4 rows at d = 128), eight loads in flight;
+//      every lane keeps G x 8 partial outputs, added up over the lanes that share columns and then over the
+//      waves through LDS, in a fixed order.
 // HBM-bound: every kept K and V row is read once (2 x count x d x 2 bytes per head), the rest stays on chip.
 #include "pkv_internal.h"
 
@@ -30,6 +31,7 @@ constexpr int kWaves = kThreads / 64;
 
 __device__ __forceinline__ bf16x8 as_frag(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
+constexpr int kMaxSplits = 16;     // key ranges per (sequence, KV head), at most
 constexpr int kTabEntries = 1026;  // block-table entries of a key range kept in LDS (pages of 4 slots or more)
 
 // Row j of (sequence b, head g) of a cache, or null if its page number is out of range.  tab: the block-table
@@ -49,7 +51,7 @@ __device__ __forceinline__ const uint16_t* cache_row(const DecodeArgs& a, const 
 // FINAL: S == 1, the result is written here; else partial results go to the workspace.
 template <int D, bool FINAL>
 __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeArgs a) {
-  constexpr int KS = D / 16, SEG = D / 8, PITCH = SEG + 1, CPL = D / 64;  // CPL: columns per lane in phase C
+  constexpr int KS = D / 16, SEG = D / 8, PITCH = SEG + 1;
   extern __shared__ float dsm[];
   // [8][chunk] logits / weights | [32 * PITCH] Q tile (16-byte slots) | [4][8][D] partial outputs | [8][2] (max, sum)
   // | [kTabEntries] block-table entries of this key range
@@ -158,56 +160,76 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
   }
   __syncthreads();
   // ---- C. values: o[h][c] = sum_j w[h][j] V[j][c] ----
-  constexpr int UN = 8;  // rows in flight per wave
-  float o[8][CPL];
+  // A lane moves 16 bytes (8 columns) of a value row per load, so a wave covers RPW rows per load and has UN of
+  // those in flight; every lane keeps G x 8 partial outputs for its columns and its share of the rows.
+  constexpr int LPR = D / 8;     // lanes per row
+  constexpr int RPW = 64 / LPR;  // rows per wave and load
+  constexpr int UN = 8;
+  const int sub = lane / LPR, col = lane - sub * LPR;
+  float o[8][8];
 #pragma unroll
   for (int h = 0; h < 8; ++h)
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) o[h][c] = 0.f;
-  for (int r0 = wave; r0 < nloc; r0 += UN * kWaves) {
-    uint32_t w[UN];
+    for (int c = 0; c < 8; ++c) o[h][c] = 0.f;
+  for (int r0 = wave * RPW; r0 < nloc; r0 += UN * kWaves * RPW) {
+    u32x4 w[UN];
     int rr[UN];
 #pragma unroll
     for (int i = 0; i < UN; ++i) {
-      const int r = r0 + i * kWaves;
+      const int r = r0 + i * kWaves * RPW + sub;
       rr[i] = r < nloc ? r : -1;
       const uint16_t* row = cache_row<D>(a, a.V, b, g, j_lo + min(r, nloc - 1), tab, q0);
       if (row == nullptr) {  // a bad page number: the row counts as absent (its weight is zero as well)
         row = a.V;
         rr[i] = -1;
       }
-      if (CPL == 2) w[i] = *reinterpret_cast<const uint32_t*>(row + 2 * lane);
-      else w[i] = row[lane];
+      w[i] = *reinterpret_cast<const u32x4*>(row + 8 * col);
     }
 #pragma unroll
     for (int i = 0; i < UN; ++i) {
-      if (rr[i] < 0) continue;  // wave-uniform
-      float v[CPL];
-      if (CPL == 2) {
-        v[0] = __uint_as_float(w[i] << 16);
-        v[CPL - 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-      } else {
-        v[0] = __uint_as_float(w[i] << 16);
+      const bool have = rr[i] >= 0;
+      if (!have) w[i] = u32x4{0u, 0u, 0u, 0u};  // whatever was read there must not reach the sums
+      float v[8];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        v[2 * c] = __uint_as_float(w[i][c] << 16);
+        v[2 * c + 1] = __uint_as_float(w[i][c] & 0xFFFF0000u);
       }
+      const int rc = have ? rr[i] : 0;
 #pragma unroll
       for (int h = 0; h < 8; ++h) {
         if (h < a.G) {
-          const float p = s_p[h * a.chunk + rr[i]];
+          const float p = have ? s_p[h * a.chunk + rc] : 0.f;
 #pragma unroll
-          for (int c = 0; c < CPL; ++c) o[h][c] = __builtin_fmaf(p, v[c], o[h][c]);
+          for (int c = 0; c < 8; ++c) o[h][c] = __builtin_fmaf(p, v[c], o[h][c]);
         }
+      }
+    }
+  }
+  // over the RPW row shares of a wave (lanes LPR apart hold the same columns), in a fixed order
+#pragma unroll
+  for (int h = 0; h < 8; ++h) {
+    if (h < a.G) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+#pragma unroll
+        for (int sft = 32; sft >= LPR; sft >>= 1) o[h][c] += __shfl_xor(o[h][c], sft);
       }
     }
   }
   // over the waves: waves 0..3 store, then waves 4..7 add to slot (wave & 3)
   for (int r = 0; r < kWaves / 4; ++r) {
-    if ((wave >> 2) == r) {
-      for (int h = 0; h < a.G; ++h)
+    if ((wave >> 2) == r && sub == 0) {
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) {
-          float* dst = &s_o[((wave & 3) * 8 + h) * D + CPL * lane + c];
-          *dst = (r == 0 ? 0.f : *dst) + o[h][c];
+      for (int h = 0; h < 8; ++h) {
+        if (h < a.G) {
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            float* dst = &s_o[((wave & 3) * 8 + h) * D + 8 * col + c];
+            *dst = (r == 0 ? 0.f : *dst) + o[h][c];
+          }
         }
+      }
     }
     __syncthreads();
   }
@@ -242,14 +264,25 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a) {
   float* out = a.out + ((size_t)b * a.Hq + (size_t)g * a.G) * D;
   for (int e = threadIdx.x; e < a.G * D; e += 256) {
     const int h = e / D;
+    // all loads first (S <= kMaxSplits, so the loops unroll): one memory round trip instead of one per range
+    float pm[kMaxSplits], pz[kMaxSplits], px[kMaxSplits];
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) {
+      const bool have = s < a.S;
+      pm[s] = have ? part_mz[s * 16 + 2 * h] : -INFINITY;
+      pz[s] = have ? part_mz[s * 16 + 2 * h + 1] : 0.f;
+      px[s] = have ? part_o[(size_t)s * 8 * D + e] : 0.f;
+    }
     float M = -INFINITY;
-    for (int s = 0; s < a.S; ++s) M = fmaxf(M, part_mz[s * 16 + 2 * h]);
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) M = fmaxf(M, pm[s]);
     const float Ms = (M == -INFINITY) ? 0.f : M;
     float z = 0.f, x = 0.f;
-    for (int s = 0; s < a.S; ++s) {
-      const float f = __builtin_amdgcn_exp2f(part_mz[s * 16 + 2 * h] - Ms);
-      z += part_mz[s * 16 + 2 * h + 1] * f;
-      x += part_o[(size_t)s * 8 * D + e] * f;
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) {
+      const float f = __builtin_amdgcn_exp2f(pm[s] - Ms);
+      z += pz[s] * f;
+      x += px[s] * f;
     }
     out[e] = z > 0.f ? x / z : 0.f;
     if (a.lse && e == h * D)
@@ -290,8 +323,8 @@ hipError_t launch(const DecodeArgs& a, hipStream_t s) {
 
 // Key ranges per (sequence, KV head): enough workgroups to fill the chip, at least 128 keys each.
 int decode_splits(int B, int Hkv, int k_cap) {
-  int S = (256 + B * Hkv - 1) / (B * Hkv);
-  if (S > 8) S = 8;
+  int S = (512 + B * Hkv - 1) / (B * Hkv);
+  if (S > kMaxSplits) S = kMaxSplits;
   const int by_len = k_cap / 128;
   if (S > by_len) S = by_len;
   return S < 1 ? 1 : S;

@@ -215,6 +215,7 @@ def test_decode_attention_rejects_bad_arguments():
     assert call(desc(d=96)) == U and call(desc(Hq=128)) == U and call(desc(k_cap=5000)) == U
     big = desc(k_cap=2048)                                              # small batch, long cache: split over key ranges
     need = lib.pkv_decode_workspace_bytes(ctypes.byref(big))
-    assert need == 2 * 8 * 8 * (8 * 128 + 16) * 4 and lib.pkv_decode_workspace_bytes(ctypes.byref(desc(B=64))) == 0
+    assert need == 2 * 8 * 16 * (8 * 128 + 16) * 4                      # 16 key ranges
+    assert lib.pkv_decode_workspace_bytes(ctypes.byref(desc(B=64))) == 0
     assert lib.pkv_decode_attention(ctypes.byref(big), 0x1000, 0x2000, 0x3000, None, 0x4000, 0x5000, None, 0x10000,
                                     need - 1, None) == binding.ERR_WORKSPACE

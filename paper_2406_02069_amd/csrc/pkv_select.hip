@@ -32,6 +32,14 @@ constexpr int TL = 16384;          // pooling tile of long prefixes (outputs per
 constexpr int HIST = 2048;         // bins of the widest digit
 constexpr int kLdsKeys = 32768;    // prefix lengths up to this keep their keys in LDS
 
+// Workgroup barrier that orders LDS traffic only.  A full __syncthreads() also waits until every global load and
+// store of the wave has completed: a memory round trip per use, where only LDS contents change hands.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Inclusive scan over the workgroup, thread order.  `scratch` holds NW entries.
 __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -82,6 +90,25 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
   // of 32 position registers kept alive for the comparisons
   const int nval = min(max((npre - pos0 + 63) >> 6, 0), kLdsKeys / NT);
   uint32_t gmax = 0u, gmin = 0xFFFFFFFFu;  // long prefixes: largest and smallest key this thread has produced
+  // long prefixes: largest key of every group of 64 positions, in LDS behind the pooling tile (if they fit)
+  constexpr int kGrpOff = 16512, kGrpCap = kLdsKeys - kGrpOff;
+  static_assert(kGrpOff >= TL + 2 * (kMaxPoolW / 2), "group maxima lie behind the tile");
+  uint32_t* grp = lkeys + kGrpOff;
+  const int ngrp = (npre + 63) >> 6;
+  const bool use_grp = !LDSKEYS && ngrp <= kGrpCap;
+  // fn(gi) for every group gi of [g_lo, g_hi), ascending, whose largest key is at least `bound`: 64 groups are
+  // tested at a time, one per lane, and the wave then walks the set bits (all arguments wave-uniform)
+  auto for_groups_at_least = [&](int g_lo, int g_hi, uint32_t bound, auto fn) {
+    for (int g0 = g_lo; g0 < g_hi; g0 += 64) {
+      const int gl = g0 + lane;
+      unsigned long long m = __ballot(gl < g_hi && grp[gl] >= bound);
+      while (m) {
+        const int bsel = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        fn(g0 + bsel);
+      }
+    }
+  };
   if (LDSKEYS) {
     // The whole prefix fits in LDS: every load of the un-pooled scores is in flight at once (one memory round
     // trip), then each thread pools its positions out of LDS; the pooled values stay in registers, already in
@@ -176,45 +203,111 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
     PKV_ST(2);
   } else {
     // Long prefix: tiles of TL outputs go through LDS, every load of a tile in flight at once; the pooled values
-    // are the keys, kept in global memory.  On the way the largest and the smallest key are noted.
+    // are the keys, kept in global memory.  On the way the largest and the smallest key are noted, and the largest
+    // key of every group of 64 consecutive positions (kept in LDS behind the tile): later passes skip the groups
+    // that cannot hold a key they look for, which is nearly all of them.
     float* lsc = reinterpret_cast<float*>(lkeys);
     constexpr int PT = TL / NT;  // outputs per thread and tile; one more load covers the 2 r halo positions
     static_assert(TL + 2 * (kMaxPoolW / 2) <= (PT + 1) * NT && TL + 2 * (kMaxPoolW / 2) <= kLdsKeys, "tile fits");
-    for (int t0 = 0; t0 < npre; t0 += TL) {
-      float v[PT + 1];
+    float v[PT + 1];
+    // the tile's scores (with the halo of r positions on both sides) into registers
+    auto request_tile = [&](int t0) {
 #pragma unroll
       for (int j = 0; j <= PT; ++j) {
         const int e = tid + NT * j, i = t0 - r + e;
         v[j] = 0.f;
-        if (e < TL + 2 * r && i >= 0 && i < npre) {
-          v[j] = raw[i];
-          for (int q = 1; q < nrb; ++q) v[j] += raw[q * rb_stride + i];
+        if (e < TL + 2 * r && i >= 0 && i < npre) v[j] = raw[i];
+      }
+      if (nrb > 1) {  // (kept apart: a loop of unknown length behind every load would make each wait for its own)
+#pragma unroll
+        for (int j = 0; j <= PT; ++j) {
+          const int e = tid + NT * j, i = t0 - r + e;
+          if (e < TL + 2 * r && i >= 0 && i < npre)
+            for (int q = 1; q < nrb; ++q) v[j] += raw[q * rb_stride + i];
         }
       }
+    };
+    request_tile(0);
+    for (int t0 = 0; t0 < npre; t0 += TL) {
+      uint32_t wmax[PT];
 #pragma unroll
       for (int j = 0; j <= PT; ++j) {
         const int e = tid + NT * j, i = t0 - r + e;
         if (e < TL + 2 * r) lsc[e] = (i >= 0 && i < npre) ? v[j] * inv_G : (is_max ? -INFINITY : 0.f);
       }
-      __syncthreads();
+      lds_barrier();
+      if (t0 + TL < npre) request_tile(t0 + TL);  // travels while this tile is pooled
+      // window of 2 RR + 1 tile entries from the output's own slot on, in ascending position order; RR < 0: the
+      // half-width is known at run time only.  (A compile-time width lets the LDS reads of all outputs of a thread
+      // go out together instead of one dependent chain after the other.)
+      auto pool_tile = [&](auto RR) {
+        constexpr int R = decltype(RR)::value;
+        const int w2 = R >= 0 ? 2 * R : 2 * r;
+        constexpr int HB = 8;  // outputs worked on together (register budget)
 #pragma unroll
-      for (int j = 0; j < PT; ++j) {
-        const int e = tid + NT * j, i = t0 + e;
-        if (i < npre) {
-          float acc = lsc[e];
-          if (is_max) {
-            for (int u = 1; u <= 2 * r; ++u) acc = fmaxf(acc, lsc[e + u]);
+        for (int j0 = 0; j0 < PT; j0 += HB) {
+          float acc[HB];
+#pragma unroll
+          for (int j = 0; j < HB; ++j) acc[j] = lsc[tid + NT * (j0 + j)];
+          if (R >= 0) {
+#pragma unroll
+            for (int u = 1; u <= (R >= 0 ? 2 * R : 0); ++u)
+#pragma unroll
+              for (int j = 0; j < HB; ++j) {
+                const float x = lsc[tid + NT * (j0 + j) + u];
+                acc[j] = is_max ? fmaxf(acc[j], x) : acc[j] + x;
+              }
           } else {
-            for (int u = 1; u <= 2 * r; ++u) acc += lsc[e + u];
-            if (r > 0) acc *= inv_w;
+            for (int u = 1; u <= w2; ++u)
+#pragma unroll
+              for (int j = 0; j < HB; ++j) {
+                const float x = lsc[tid + NT * (j0 + j) + u];
+                acc[j] = is_max ? fmaxf(acc[j], x) : acc[j] + x;
+              }
           }
-          pooled[i] = acc;
-          gmax = max(gmax, __float_as_uint(acc));
-          gmin = min(gmin, __float_as_uint(acc));
+#pragma unroll
+          for (int j = 0; j < HB; ++j) {
+            const int i = t0 + tid + NT * (j0 + j);
+            wmax[j0 + j] = 0u;
+            if (i < npre) {
+              const float y = (!is_max && w2 > 0) ? acc[j] * inv_w : acc[j];
+              pooled[i] = y;
+              wmax[j0 + j] = __float_as_uint(y);
+              gmax = max(gmax, wmax[j0 + j]);
+              gmin = min(gmin, wmax[j0 + j]);
+            }
+          }
+        }
+      };
+      using std::integral_constant;
+      if (r == 0) pool_tile(integral_constant<int, 0>{});
+      else if (r == 1) pool_tile(integral_constant<int, 1>{});
+      else if (r == 2) pool_tile(integral_constant<int, 2>{});
+      else if (r == 3) pool_tile(integral_constant<int, 3>{});
+      else pool_tile(integral_constant<int, -1>{});
+      if (use_grp) {  // the 64 lanes of a wave hold 64 consecutive positions; all PT reductions step by step together
+#pragma unroll
+        for (int j0 = 0; j0 < PT; j0 += 8) {
+#pragma unroll
+          for (int sft = 32; sft > 0; sft >>= 1) {
+            uint32_t t[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) t[j] = (uint32_t)__shfl_xor((int)wmax[j0 + j], sft);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) wmax[j0 + j] = max(wmax[j0 + j], t[j]);
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < PT; ++j) {
+          const int gi = (t0 + NT * j) / 64 + wave;
+          if (lane == 0 && gi < ngrp) grp[gi] = wmax[j];
         }
       }
-      __syncthreads();
+      lds_barrier();  // (the tile is rewritten next; the pooled values are read only after the loop)
     }
+    __syncthreads();  // the keys in global memory and the group maxima are complete
+    PKV_ST(1);
+    PKV_ST(2);
   }
 
   if (kk > 0) {
@@ -359,25 +452,41 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       int top = (diff == 0u) ? 0 : 32 - __clz((int)diff);  // undecided low bits
       prefix = (top >= 32) ? 0u : (gmax >> top) << top;
       constexpr int NB = 16;  // keys per thread and round
+      bool first_level = true;
       while (top > 0) {
         const int nb = min(11, top), shift = top - nb;
         const uint32_t dmask = (1u << nb) - 1u;
         for (int e = tid; e < HIST; e += NT) hist[e] = 0;
         __syncthreads();
-        for (int i0 = 0; i0 < npre; i0 += NB * NT) {
-          uint32_t key[NB];
+        if (use_grp && !first_level) {
+          // an open key is at least `prefix` (its decided bits, zeros below): only groups whose largest key reaches
+          // that can hold one
+          const int gw = (ngrp + NW - 1) / NW;  // groups per wave
+          for_groups_at_least(wave * gw, min(wave * gw + gw, ngrp), prefix, [&](int gi) {
+            const int i = 64 * gi + lane;
+            const uint32_t key = i < npre ? gkeys[i] : 0u;
+            if (i < npre && (key >> top) == (prefix >> top)) atomicAdd(&hist[(key >> shift) & dmask], 1u);
+          });
+        } else {
+          for (int i0 = 0; i0 < npre; i0 += NB * NT) {
+            uint32_t key[NB];
 #pragma unroll
-          for (int j = 0; j < NB; ++j) {
-            const int i = i0 + tid + NT * j;
-            key[j] = i < npre ? gkeys[i] : 0u;
-          }
+            for (int j = 0; j < NB; ++j) {
+              const int i = i0 + tid + NT * j;
+              key[j] = i < npre ? gkeys[i] : 0u;
+            }
 #pragma unroll
-          for (int j = 0; j < NB; ++j) {
-            const int i = i0 + tid + NT * j;
-            const bool open = top >= 32 || (key[j] >> top) == (prefix >> top);
-            if (i < npre && open) atomicAdd(&hist[(key[j] >> shift) & dmask], 1u);
+            for (int j = 0; j < NB; ++j) {
+              const int i = i0 + tid + NT * j;
+              const bool open = top >= 32 || (key[j] >> top) == (prefix >> top);
+              if (i < npre && open) atomicAdd(&hist[(key[j] >> shift) & dmask], 1u);
+            }
           }
         }
+#ifdef PKV_SEL_TIMING
+        if (first_level) { __syncthreads(); PKV_ST(5); }
+#endif
+        first_level = false;
         __syncthreads();
         // thread t owns bins 2t, 2t+1; suffix sums over the bins owned by higher threads
         const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
@@ -452,24 +561,34 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
         eq_before += __popcll(beq);
       }
     } else {
-      // every wave owns a contiguous range of positions; two passes over its keys (count, then emit), eight
-      // groups of 64 positions per round with their loads in flight together
+      // every wave owns a contiguous range of positions; two passes over its keys (count, then emit).  With the
+      // group maxima at hand only the groups that hold a key >= T are read; else eight groups of 64 positions per
+      // round with their loads in flight together.
       constexpr int NE = 8;
       const int cw = ((npre + NW - 1) / NW + 63) & ~63;  // positions per wave, multiple of 64
       const int w0 = min(wave * cw, npre), w1 = min(w0 + cw, npre);
       uint32_t cgt = 0, ceq = 0;
-      for (int base = w0; base < w1; base += 64 * NE) {
-        uint32_t key[NE];
+      if (use_grp) {
+        for_groups_at_least(w0 >> 6, w0 < w1 ? (w1 + 63) >> 6 : w0 >> 6, T, [&](int gi) {
+          const int i = 64 * gi + lane;
+          const uint32_t key = i < w1 ? gkeys[i] : 0u;
+          cgt += __popcll(__ballot(i < w1 && key > T));
+          ceq += __popcll(__ballot(i < w1 && key == T));
+        });
+      } else {
+        for (int base = w0; base < w1; base += 64 * NE) {
+          uint32_t key[NE];
 #pragma unroll
-        for (int j = 0; j < NE; ++j) {
-          const int i = base + 64 * j + lane;
-          key[j] = i < w1 ? gkeys[i] : 0u;
-        }
+          for (int j = 0; j < NE; ++j) {
+            const int i = base + 64 * j + lane;
+            key[j] = i < w1 ? gkeys[i] : 0u;
+          }
 #pragma unroll
-        for (int j = 0; j < NE; ++j) {
-          const int i = base + 64 * j + lane;
-          cgt += __popcll(__ballot(i < w1 && key[j] > T));
-          ceq += __popcll(__ballot(i < w1 && key[j] == T));
+          for (int j = 0; j < NE; ++j) {
+            const int i = base + 64 * j + lane;
+            cgt += __popcll(__ballot(i < w1 && key[j] > T));
+            ceq += __popcll(__ballot(i < w1 && key[j] == T));
+          }
         }
       }
       __syncthreads();
@@ -488,25 +607,34 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       }
       const uint32_t need_eq = (uint32_t)kk - gt_total;  // keys equal to T to take, lowest positions first (>= 1)
       const unsigned long long lt_mask = (1ull << lane) - 1ull;
-      for (int base = w0; base < w1; base += 64 * NE) {
-        uint32_t key[NE];
+      // the 64 positions from `base` on, their keys in `key`: kept ones go to their ranks
+      auto emit64 = [&](int base, uint32_t key) {
+        const int i = base + lane;
+        const bool gt = i < w1 && key > T, eq = i < w1 && key == T;
+        const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+        if ((bgt | beq) == 0) return;
+        const uint32_t gtb = gt_before + __popcll(bgt & lt_mask);
+        const uint32_t eqb = eq_before + __popcll(beq & lt_mask);
+        if (gt) idx[gtb + min(eqb, need_eq)] = i;
+        if (eq && eqb < need_eq) idx[gtb + eqb] = i;
+        gt_before += __popcll(bgt);
+        eq_before += __popcll(beq);
+      };
+      if (use_grp) {
+        for_groups_at_least(w0 >> 6, w0 < w1 ? (w1 + 63) >> 6 : w0 >> 6, T, [&](int gi) {
+          const int i = 64 * gi + lane;
+          emit64(64 * gi, i < w1 ? gkeys[i] : 0u);
+        });
+      } else {
+        for (int base = w0; base < w1; base += 64 * NE) {
+          uint32_t key[NE];
 #pragma unroll
-        for (int j = 0; j < NE; ++j) {
-          const int i = base + 64 * j + lane;
-          key[j] = i < w1 ? gkeys[i] : 0u;
-        }
+          for (int j = 0; j < NE; ++j) {
+            const int i = base + 64 * j + lane;
+            key[j] = i < w1 ? gkeys[i] : 0u;
+          }
 #pragma unroll
-        for (int j = 0; j < NE; ++j) {
-          const int i = base + 64 * j + lane;
-          const bool gt = i < w1 && key[j] > T, eq = i < w1 && key[j] == T;
-          const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
-          if ((bgt | beq) == 0) continue;
-          const uint32_t gtb = gt_before + __popcll(bgt & lt_mask);
-          const uint32_t eqb = eq_before + __popcll(beq & lt_mask);
-          if (gt) idx[gtb + min(eqb, need_eq)] = i;
-          if (eq && eqb < need_eq) idx[gtb + eqb] = i;
-          gt_before += __popcll(bgt);
-          eq_before += __popcll(beq);
+          for (int j = 0; j < NE; ++j) emit64(base + 64 * j, key[j]);
         }
       }
     }

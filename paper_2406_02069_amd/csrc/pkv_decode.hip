@@ -298,7 +298,10 @@ size_t lds_bytes(int d, int chunk) {
 template <int D>
 hipError_t launch(const DecodeArgs& a, hipStream_t s) {
   const size_t lds = lds_bytes(D, a.chunk);
-  static size_t granted[2] = {0, 0};
+  static size_t granted_all[kMaxDevices][2];  // per device: the limit set so far for each of the two kernels
+  const int dev = current_device_slot();
+  if (dev < 0) return hipErrorInvalidDevice;
+  size_t* granted = granted_all[dev];
   const int fin = a.S == 1 ? 1 : 0;
   if (lds > granted[fin]) {  // raise the dynamic LDS limit when a larger cache comes along (no allocation)
     const void* f = fin ? reinterpret_cast<const void*>(decode_partial_kernel<D, true>)

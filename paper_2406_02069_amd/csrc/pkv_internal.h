@@ -176,6 +176,14 @@ struct DecodeArgs {
 int decode_splits(int B, int Hkv, int k_cap);
 hipError_t launch_decode_attention(const DecodeArgs& a, hipStream_t s);
 
+// Index of the current device for per-device launch state (dynamic LDS limits are set per device), or -1.
+constexpr int kMaxDevices = 64;
+inline int current_device_slot() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+  return dev;
+}
+
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s);
 hipError_t launch_recall(const RecallArgs& a, int nlayers, hipStream_t s);
 hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipStream_t s);

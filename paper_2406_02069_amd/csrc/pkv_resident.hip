@@ -975,12 +975,14 @@ template <int D, bool LSE>
 static hipError_t launch_resident(const ResidentArgs& a, hipStream_t s) {
   constexpr int SEG = D / 8;
   const size_t dyn = (size_t)2 * kRowBlock * lds_pitch<SEG>() * sizeof(u32x4);  // two Q buffers
-  static bool attr_set = false;
-  if (!attr_set) {  // raise the dynamic LDS limit once (idempotent; no allocation)
+  static bool attr_set[kMaxDevices];
+  const int dev = current_device_slot();
+  if (dev < 0) return hipErrorInvalidDevice;
+  if (!attr_set[dev]) {  // raise the dynamic LDS limit once per device (idempotent; no allocation)
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_resident_kernel<D, LSE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   hipLaunchKernelGGL((score_resident_kernel<D, LSE>), dim3(kResidentGrid), dim3(kThreads), dyn, s, a);
   return hipGetLastError();

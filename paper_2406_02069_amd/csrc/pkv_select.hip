@@ -686,13 +686,15 @@ __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatch
 }  // namespace
 
 hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipStream_t s) {
-  static bool attr_set = false;
+  static bool attr_set[kMaxDevices];
   const size_t dyn = (size_t)kLdsKeys * sizeof(uint32_t);
-  if (!attr_set) {  // allow 128 KB of dynamic LDS (idempotent; no allocation)
+  const int dev = current_device_slot();
+  if (dev < 0) return hipErrorInvalidDevice;
+  if (!attr_set[dev]) {  // allow 128 KB of dynamic LDS, once per device (idempotent; no allocation)
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pool_select_batch_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   hipLaunchKernelGGL(pool_select_batch_kernel, dim3(nlayers * a.B * a.Hkv), dim3(NT), dyn, s, a);
   return hipGetLastError();

@@ -222,10 +222,11 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       ra.ngroups = plan.ngroups; ra.UPG = plan.UPG;
       ra.stagger = resident_stagger(lse_mode ? 0 : 250);
       ra.spin_limit = resident_spin_limit();
-      // every part of a group takes part in every unit when all sequences have the full length; worth it when a
-      // unit has enough parts to spread the rows over (test hook: PKV_FOLD=counter keeps the arrival counter)
+      // the tagged exchange (every part of a group takes part in every unit, also one that lies beyond the end of a
+      // shorter sequence) is worth it when a unit has enough parts to spread the rows over (test hook:
+      // PKV_FOLD=counter keeps the arrival counter)
       const char* fold = getenv("PKV_FOLD");
-      ra.tagged = (!lse_mode && seq_lens == nullptr && plan.TPU >= 16 && !(fold && !strcmp(fold, "counter"))) ? 1 : 0;
+      ra.tagged = (!lse_mode && plan.TPU >= 16 && !(fold && !strcmp(fold, "counter"))) ? 1 : 0;
       ra.part_words = (int32_t)((size_t)plan.ngroups * plan.UPG * plan.TPU * plan.res_Rpad * 2);
       ra.set1_w = resident_set1_weight(ra.tagged != 0);
       ra.d = d.d;

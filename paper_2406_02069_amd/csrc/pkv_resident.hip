@@ -24,7 +24,8 @@
 //   3. arrives at the unit's counter.  The last part to arrive folds all parts into the per-row
 //      normaliser c_r = max + log2(sum) and publishes it, tagged with the unit number; the others poll
 //      the tagged words.  (Agent-scope relaxed atomics: written through, never served from a stale line.)
-//      When every part takes part in every unit (no ragged batch) there is no counter: the statistics
+//      When a unit has 16 parts or more, every part takes part in every unit of its group (one beyond the end
+//      of a shorter sequence contributes neutral statistics) and there is no counter: the statistics
 //      words carry a phase bit, and part p folds the rows p, p + nparts, ... as soon as their words show
 //      it.
 //   4. sweep 2: same products from the same registers, s_i = sum_r exp2(kappa q_r.k_i - c_r), written
@@ -247,12 +248,14 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         n = n < 0 ? 0 : (n > a.N ? a.N : n);
       }
       if (a.layer[l].k_l >= n) continue;  // whole sequence kept: no scores needed (uniform over the unit)
-      if (key0 >= n) continue;            // no keys here; this part is not counted at the barrier
+      // no keys here: with the arrival counter this part is not counted and moves on; with the tagged exchange
+      // every part takes part in every unit of its group (neutral statistics, its share of the fold, the wait)
+      if (!a.tagged && key0 >= n) continue;
       d.u = u;
       d.j = j;
       d.n = n;
       d.npre = n - a.alpha;
-      d.nparts = (n + kResidentKeys - 1) / kResidentKeys;
+      d.nparts = a.tagged ? a.TPU : (n + kResidentKeys - 1) / kResidentKeys;
       d.Q = a.layer[l].Q + (size_t)b * a.q_sb + (size_t)(g * a.G) * a.q_sh;
       d.K = a.layer[l].K + (size_t)b * a.kv_sb + (size_t)g * a.kv_sh;
       if (LSE) d.lse = a.layer[l].lse + ((size_t)b * a.Hq + (size_t)g * a.G) * a.alpha;

@@ -72,6 +72,13 @@ def test_config3_mistral_ragged_batch():
     _full(3, 1)
 
 
+def test_config3_mistral_ragged_batch_with_the_arrival_counter(monkeypatch):
+    # the exchange of softmax statistics through the arrival counter (the default for units of fewer than 16 parts)
+    # at a size where the tagged exchange would be used
+    monkeypatch.setenv("PKV_FOLD", "counter")
+    _full(3, 1)
+
+
 def test_config4_llama3_70b_32k():
     _full(4, 1)
 

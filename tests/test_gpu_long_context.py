@@ -139,3 +139,22 @@ def test_long_prefix_with_non_finite_scores_stays_in_bounds():
     ref = binding.compress_layer(Q, Kc, V, k_l, synth.POOL_MAX, 7, want_scores=True)
     torch.cuda.synchronize()
     assert np.array_equal(idx[0, 1], ref[2][0, 1].cpu().numpy())   # the other head is unaffected
+
+
+@pytest.mark.parametrize("d,Hq,Hkv,alpha,N", [(64, 16, 2, 64, 70000),    # 512 query rows per KV head: four row blocks
+                                              (128, 4, 4, 8, 50000),     # 8 rows: padded row tile, MHA
+                                              (64, 6, 2, 37, 33000)])    # odd window, just beyond the in-LDS selection
+def test_other_geometries_long_context(d, Hq, Hkv, alpha, N):
+    g = torch.Generator(device=DEV).manual_seed(N + d)
+    Q = torch.randn(1, Hq, alpha, d, generator=g, device=DEV).to(torch.bfloat16)
+    K = torch.randn(1, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    V = torch.randn(1, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16)
+    k_l = alpha + 333
+    out = binding.compress_layer(Q, K, V, k_l, synth.POOL_MAX, 7, want_scores=True)
+    torch.cuda.synchronize()
+    compare_layer(Q, K, V, k_l, alpha, synth.POOL_MAX, 7, None, out)
+    lse = prefill_stub.window_lse(Q, K, None)
+    out = binding.compress_layers_lse([Q], [K], [V], [lse], [k_l], synth.POOL_AVG, 5, want_scores=True)[0]
+    torch.cuda.synchronize()
+    ref = pkv_oracle.compress_layer(Q, K, V, k_l, alpha, synth.POOL_AVG, 5, lse=lse.cpu().numpy())
+    compare_layer(Q, K, V, k_l, alpha, synth.POOL_AVG, 5, None, out, ref=ref)

@@ -46,3 +46,35 @@ def test_random_shape(seed, path, monkeypatch):
     out = binding.compress_layer(Q, K, V, k_l, pool, pw, seq_lens=lens_dev, want_scores=True)
     torch.cuda.synchronize()
     compare_layer(Q, K, V, k_l, alpha, pool, pw, lens, out)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_ragged_batch_with_many_parts(seed):
+    """Units of 16 parts or more in a ragged batch: the tagged exchange of the softmax statistics with parts that lie
+    beyond the end of a shorter sequence (they take part with neutral statistics), several layers so that every
+    group of workgroups works through more than one unit."""
+    rs = np.random.RandomState(300 + seed)
+    d = int(rs.choice([64, 128]))
+    Hkv = int(rs.choice([1, 2, 4]))
+    G = int(rs.choice([1, 4, 8]))
+    alpha = int(rs.choice([8, 16, 32]))
+    B = 3
+    N = int(rs.randint(8192, 14000))
+    L = int(rs.randint(2, 5))
+    pool, pw = [(synth.POOL_MAX, 7), (synth.POOL_AVG, 5), (synth.POOL_NONE, 1)][rs.randint(3)]
+    lens = np.array([N, rs.randint(alpha + 1, N), rs.choice([0, alpha - 1, 513, N // 2])], dtype=np.int32)
+    lens = lens[rs.permutation(3)]
+    ks = [int(rs.randint(alpha, 2000)) for _ in range(L)]
+    print("ragged case", seed, dict(d=d, Hkv=Hkv, G=G, alpha=alpha, N=N, L=L, pool=pool, pw=pw, lens=lens.tolist(), ks=ks),
+          flush=True)
+    g = torch.Generator(device=DEV).manual_seed(900 + seed)
+    Qs = [torch.randn(B, Hkv * G, alpha, d, generator=g, device=DEV).to(torch.bfloat16) for _ in range(L)]
+    Ks = [torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16) for _ in range(L)]
+    Vs = [torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16) for _ in range(L)]
+    for K in Ks:
+        for b in range(B):
+            K[b, :, int(lens[b]):] = float("nan")   # never read
+    outs = binding.compress_layers(Qs, Ks, Vs, ks, pool, pw, seq_lens=torch.from_numpy(lens).to(DEV), want_scores=True)
+    torch.cuda.synchronize()
+    for l in sorted({0, L - 1}):
+        compare_layer(Qs[l], Ks[l], Vs[l], ks[l], alpha, pool, pw, lens, outs[l])

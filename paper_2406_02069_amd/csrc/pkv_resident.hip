@@ -966,10 +966,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
 #endif
 }
 
+// Clears n words at p and n2 words at p2 (p2 16-byte aligned, n2 a multiple of 4: four words per thread there).
 __global__ void zero_kernel(int32_t* p, int n, int32_t* p2, int n2) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
-  else if (i - n < n2) p2[i - n] = 0;
+  else if (4 * (i - n) < n2) reinterpret_cast<int4*>(p2)[i - n] = make_int4(0, 0, 0, 0);
 }
 
 }  // namespace
@@ -995,8 +996,8 @@ hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s) {
   // the counters, the error word and the tagged normaliser words must start at zero (with supplied denominators
   // only the error word is looked at, by the selection kernel)
   // (tagged mode: the per-part statistics as well, whose words carry a phase bit)
-  const int nz = a.sync_words, nz2 = a.tagged ? a.part_words : 0;
-  hipLaunchKernelGGL(zero_kernel, dim3((nz + nz2 + 255) / 256), dim3(256), 0, s, a.zero_base, nz,
+  const int nz = a.sync_words, nz2 = a.tagged ? a.part_words : 0;  // (part_words: a multiple of 256)
+  hipLaunchKernelGGL(zero_kernel, dim3((nz + nz2 / 4 + 255) / 256), dim3(256), 0, s, a.zero_base, nz,
                      reinterpret_cast<int32_t*>(a.part), nz2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -40,6 +40,21 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Largest of a value over the 64 lanes of a wave, valid in lane 63.  Data-parallel-primitive row operations (no LDS
+// traffic): running maximum within each row of 16 lanes by shifts of 1, 2, 4, 8 (lanes without a source take 0),
+// then the last lane of row 0 / row 2 is handed to row 1 / row 3, and lane 31 to rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_max_lane63(uint32_t v) {
+#define PKV_DPP_MAX(ctrl, rows) v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, rows, 0xF, false))
+  PKV_DPP_MAX(0x111, 0xF);  // row_shr:1
+  PKV_DPP_MAX(0x112, 0xF);  // row_shr:2
+  PKV_DPP_MAX(0x114, 0xF);  // row_shr:4
+  PKV_DPP_MAX(0x118, 0xF);  // row_shr:8
+  PKV_DPP_MAX(0x142, 0xA);  // row_bcast:15 into rows 1 and 3
+  PKV_DPP_MAX(0x143, 0xC);  // row_bcast:31 into rows 2 and 3
+#undef PKV_DPP_MAX
+  return v;
+}
+
 // Inclusive scan over the workgroup, thread order.  `scratch` holds NW entries.
 __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -285,22 +300,12 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       else if (r == 2) pool_tile(integral_constant<int, 2>{});
       else if (r == 3) pool_tile(integral_constant<int, 3>{});
       else pool_tile(integral_constant<int, -1>{});
-      if (use_grp) {  // the 64 lanes of a wave hold 64 consecutive positions; all PT reductions step by step together
-#pragma unroll
-        for (int j0 = 0; j0 < PT; j0 += 8) {
-#pragma unroll
-          for (int sft = 32; sft > 0; sft >>= 1) {
-            uint32_t t[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) t[j] = (uint32_t)__shfl_xor((int)wmax[j0 + j], sft);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) wmax[j0 + j] = max(wmax[j0 + j], t[j]);
-          }
-        }
+      if (use_grp) {  // the 64 lanes of a wave hold 64 consecutive positions
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
+          const uint32_t m = wave_max_lane63(wmax[j]);
           const int gi = (t0 + NT * j) / 64 + wave;
-          if (lane == 0 && gi < ngrp) grp[gi] = wmax[j];
+          if (lane == 63 && gi < ngrp) grp[gi] = m;
         }
       }
       lds_barrier();  // (the tile is rewritten next; the pooled values are read only after the loop)

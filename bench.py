@@ -131,7 +131,7 @@ def main():
             layers_host[l] = (Q.cpu(), K.cpu(), V.cpu())
     lses = None
     if args.lse:  # what the prefill attention kernel would hand over; an input, prepared before timing
-        from paper_2406_02069_amd import prefill_stub
+        from tests import prefill_stub
         lses = [prefill_stub.window_lse(Qs[l], Ks[l], lens) for l in range(w.L)]
     paged = None
     if args.page_size > 0:  # every layer its own pool and block table; pages handed out in a seeded random order

@@ -24,16 +24,24 @@
  *    allocate or free memory.  Results are deterministic: the same inputs
  *    give bit-identical outputs.
  *  - Inputs are never modified.
- *  - Environment variables read at call time (tuning and test hooks; none is
- *    needed in production): PKV_SCORE_PATH=stream forces the per-layer
- *    scoring kernels that read K twice instead of the register-resident one;
- *    PKV_STAGGER=<ticks of 10 ns> sets the start offset between workgroup
- *    groups of the resident kernel; PKV_SET1_W=<1..31> the share (of 32)
- *    of the units that the groups of second workgroups take;
- *    PKV_FOLD=counter keeps the arrival counter in the exchange of softmax
- *    statistics where the tagged exchange would be used;
- *    PKV_SPIN_LIMIT=<probes> bounds its waits (0: give up at once, which a
- *    test uses to see count_out = -1).
+ *  - The library keeps no state between calls and reads no environment
+ *    variables.  (The per-device attributes of its kernels are set on first
+ *    use.)
+ *  - Exclusive use of the device.  Whenever a device with at least 256
+ *    compute units is given a shape the register-resident scoring kernel
+ *    serves (G*alpha <= 512, N <= 262144) without supplied softmax
+ *    denominators, that kernel's 512 workgroups exchange softmax statistics
+ *    with each other and must all be resident on the device at the same
+ *    time; they fill it completely (registers and LDS of every compute
+ *    unit).  The caller must therefore not run other kernels on the device
+ *    while such a call executes: no second compress call on another stream,
+ *    no other tenant.  Work queued behind it on the same stream is fine.
+ *    If the workgroups cannot all be resident, the waits between them are
+ *    given up after about 50 ms of wall-clock time each, the call completes,
+ *    and every count_out of the call reads -1 (see pkv_compress_layer); it
+ *    never hangs.  The variants with supplied denominators
+ *    (pkv_compress_layers_lse) have no such waits and share the device
+ *    freely.
  */
 #ifndef PKV_H_
 #define PKV_H_
@@ -115,7 +123,8 @@ typedef struct {
   int32_t k_l;    /* this layer's budget including the window, >= alpha      */
   int32_t pool;   /* pkv_pool                                                */
   int32_t pool_w; /* pooling width, odd, 1..63 (1 == no pooling)             */
-  int32_t reserved; /* must be 0                                             */
+  int32_t flags;  /* 0.  (Test and measurement switches, pkv_measure.h:
+                     bits outside PKV_FLAG_ALL -> PKV_ERR_INVALID_ARG)       */
   int64_t q_sb, q_sh, q_st;    /* strides of Q_win [B, Hq, alpha, d]         */
   int64_t kv_sb, kv_sh, kv_st; /* strides of K and of V [B, Hkv, N, d]       */
   int64_t o_sb, o_sh, o_st;    /* strides of K_out and V_out
@@ -177,11 +186,12 @@ size_t pkv_workspace_bytes(const pkv_layer_desc* desc, int32_t L);
  * workspace  DEVICE, 256-byte aligned, >= pkv_workspace_bytes(desc, 1) bytes;
  *            contents on entry are irrelevant, contents on exit undefined
  *            (except as pkv_attention_recall uses them).
- *            Concurrent calls must use distinct workspaces.
+ *            Calls that may overlap in time need distinct workspaces (and
+ *            see "Exclusive use of the device" above).
  * stream     hipStream_t.
  *
  * Errors: PKV_ERR_INVALID_ARG (NULL required pointer, shape/stride rules
- * above violated, reserved != 0), PKV_ERR_UNSUPPORTED (d not 64/128,
+ * above violated, unknown flags), PKV_ERR_UNSUPPORTED (d not 64/128,
  * alpha > 64, pool_w > 63), PKV_ERR_WORKSPACE, PKV_ERR_HIP.
  */
 int pkv_compress_layer(const pkv_layer_desc* desc, const void* Q_win,
@@ -374,61 +384,6 @@ int pkv_decode_attention(const pkv_decode_desc* desc, const void* q,
                          const int32_t* block_table, const int32_t* count,
                          float* out, float* lse_out, void* workspace,
                          size_t workspace_bytes, void* stream);
-
-/*
- * Measurement aid (no part of the method): pkv_compress_layers (lse NULL)
- * or pkv_compress_layers_lse (lse given), compact (paged NULL) or paged
- * output (paged and block_tables given; K_out / V_out are then the page
- * pools), with the caller's HIP events recorded around the kernels, so that
- * a benchmark can attribute device time to each kernel without a profiler.
- *
- * events     HOST array of n_events hipEvent_t handles created by the caller
- *            with timing enabled.  events[0] is recorded on `stream` before
- *            the first kernel, events[i] after the i-th kernel launched.
- * kernel_ids HOST int32[n_events - 1], written: kernel_ids[i-1] is the
- *            pkv_kernel_id of the kernel between events[i-1] and events[i].
- * n_used     HOST int32, written: number of events recorded (kernels + 1).
- * The call does not synchronise; the caller synchronises the stream and
- * reads hipEventElapsedTime(events[i-1], events[i]).
- * Errors: as pkv_compress_layers; n_events too small for the launch
- * sequence (5 kernels per layer + 1) -> PKV_ERR_INVALID_ARG.
- */
-typedef enum {
-  PKV_KERNEL_SCORE_STATS = 0, /* sweep 1 over K: per-row softmax statistics */
-  PKV_KERNEL_SCORE_FINALIZE = 1,
-  PKV_KERNEL_SCORE_ACCUM = 2, /* sweep 2 over K: per-key window scores      */
-  PKV_KERNEL_POOL_SELECT = 3,
-  PKV_KERNEL_GATHER = 4,
-  PKV_KERNEL_SCORE_RESIDENT = 5 /* both sweeps, K held in registers (all layers) */
-} pkv_kernel_id;
-
-int pkv_compress_layers_profiled(
-    int32_t L, const pkv_layer_desc* descs, const void* const* Q_win,
-    const void* const* K, const void* const* V, const float* const* lse,
-    const int32_t* seq_lens, const pkv_paged_desc* paged,
-    const int32_t* const* block_tables,
-    void* const* K_out, void* const* V_out, int32_t* const* idx_out,
-    int32_t* const* count_out, float* const* scores_out, void* workspace,
-    size_t workspace_bytes, void* stream, void* const* events,
-    int32_t n_events, int32_t* kernel_ids, int32_t* n_used);
-
-/*
- * Measurement aid (no part of the method): streams `bytes` bytes starting at
- * `buf` from memory once, with 16-byte loads by a grid that fills the chip,
- * and discards them.  Timed by the caller (events or a synchronised clock), it
- * gives the read bandwidth this device reaches on a plain scan: the measured
- * ceiling beside the published peak in the roofline of the scoring kernel.
- *
- * buf    DEVICE pointer, 16-byte aligned, readable for `bytes` bytes.
- * bytes  multiple of 16, > 0.
- * sink   DEVICE uint32, written only if a checksum of the data takes one
- *        particular value (it keeps the loads alive); contents meaningless.
- * stream hipStream_t as void*.  Asynchronous; never allocates.
- * Returns PKV_OK, PKV_ERR_INVALID_ARG (null / misaligned / size) or
- * PKV_ERR_HIP.
- */
-int pkv_probe_read(const void* buf, size_t bytes, uint32_t* sink,
-                   void* stream);
 
 /* Static, NUL-terminated description of a pkv_status value.  HOST only. */
 const char* pkv_status_string(int status);

@@ -19,6 +19,11 @@ LIB_PATH = os.path.join(_HERE, "libpkv.so")
 POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
+# pkv_layer_desc.flags (include/pkv_measure.h): test and measurement switches, 0 in production.  Descriptors made
+# by this module carry DESC_FLAGS, which tests set to run the other scoring path or exchange.
+FLAG_STREAM_SCORING, FLAG_COUNTER_EXCHANGE, FLAG_NO_WAIT = 1, 2, 4
+DESC_FLAGS = 0
+
 EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers",
            "pkv_compress_layers_lse", "pkv_compress_layers_paged", "pkv_compress_layers_profiled",
            "pkv_budgets_schedule", "pkv_attention_recall", "pkv_decode_attention", "pkv_decode_workspace_bytes", "pkv_probe_read", "pkv_status_string"]
@@ -32,7 +37,7 @@ class PkvError(RuntimeError):
 
 class LayerDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("B", "Hq", "Hkv", "d", "N", "alpha", "k_l", "pool", "pool_w", "reserved")] + \
+                ("B", "Hq", "Hkv", "d", "N", "alpha", "k_l", "pool", "pool_w", "flags")] + \
                [(n, ctypes.c_int64) for n in
                 ("q_sb", "q_sh", "q_st", "kv_sb", "kv_sh", "kv_st", "o_sb", "o_sh", "o_st")]
 
@@ -124,7 +129,7 @@ def make_desc(Q_win: torch.Tensor, K: torch.Tensor, k_l: int, pool: int, pool_w:
         o = (K_out.stride(0), K_out.stride(1), K_out.stride(2))
     else:
         o = (Hkv * k_cap * d, k_cap * d, d)
-    return LayerDesc(B, Hq, Hkv, d, N, alpha, int(k_l), int(pool), int(pool_w), 0,
+    return LayerDesc(B, Hq, Hkv, d, N, alpha, int(k_l), int(pool), int(pool_w), int(DESC_FLAGS),
                      Q_win.stride(0), Q_win.stride(1), Q_win.stride(2),
                      K.stride(0), K.stride(1), K.stride(2), o[0], o[1], o[2])
 

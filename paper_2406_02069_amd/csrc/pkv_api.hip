@@ -4,6 +4,9 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
+#include <vector>
+
 #include "pkv_internal.h"
 
 namespace pkv {
@@ -62,8 +65,6 @@ Plan make_plan(const pkv_layer_desc& d, int L) {
   off += align256(raw_res > raw_str ? raw_res : raw_str);
   p.off_pooled = off;
   off += align256(U * d.N * sizeof(float));
-  p.off_dbg = off;
-  off += align256(((size_t)kResidentGrid * 16 + 1024 + 256 * 8) * sizeof(long long));
   p.total = off;
   return p;
 }
@@ -73,7 +74,7 @@ static int check_desc(const pkv_layer_desc* d) {
   if (d->B < 1 || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0 || d->N < 1 || d->d < 1) return PKV_ERR_INVALID_ARG;
   if (d->alpha < 1 || d->k_l < d->alpha) return PKV_ERR_INVALID_ARG;
   if (d->pool != PKV_POOL_NONE && d->pool != PKV_POOL_MAX && d->pool != PKV_POOL_AVG) return PKV_ERR_INVALID_ARG;
-  if (d->pool_w < 1 || d->pool_w % 2 == 0 || d->reserved != 0) return PKV_ERR_INVALID_ARG;
+  if (d->pool_w < 1 || d->pool_w % 2 == 0 || (d->flags & ~(int32_t)PKV_FLAG_ALL) != 0) return PKV_ERR_INVALID_ARG;
   const int64_t strides[9] = {d->q_sb, d->q_sh, d->q_st, d->kv_sb, d->kv_sh, d->kv_st, d->o_sb, d->o_sh, d->o_st};
   for (int i = 0; i < 9; ++i)
     if (strides[i] < 0 || strides[i] % 8 != 0) return PKV_ERR_INVALID_ARG;  // 16-byte row alignment
@@ -144,35 +145,22 @@ static bool device_fits_resident() {
   return cached[dev] == 1;
 }
 
-// Start offset between consecutive workgroup groups, in 10 ns ticks (tuning hook: PKV_STAGGER).
-static int resident_stagger(int dflt) {
-  if (const char* e = getenv("PKV_STAGGER")) return atoi(e);
-  return dflt;
-}
+// Start offset between consecutive workgroup groups of the two-sweep resident kernel, in 10 ns ticks.
+constexpr int kResidentStagger = 250;
 
-// Share (of 32) of a group pair's units that the group of second workgroups takes (tuning hook: PKV_SET1_W).
-static int resident_set1_weight(bool tagged) {
-  if (const char* e = getenv("PKV_SET1_W")) {
-    const int w = atoi(e);
-    return w < 1 ? 1 : (w > 31 ? 31 : w);
-  }
-  // measured on the 32k workload: with the arrival counter 15 beats equal shares (16) by 1.7 %; with the tagged
-  // exchange the second workgroups wait less and equal shares are ahead by 0.7 %
-  return tagged ? 16 : 15;
-}
+// Share (of 32) of a group pair's units that the group of second workgroups takes.  Measured on the 32k workload:
+// with the arrival counter 15 beats equal shares (16) by 1.7 %; with the tagged exchange the second workgroups wait
+// less and equal shares are ahead by 0.7 %.
+static int resident_set1_weight(bool tagged) { return tagged ? 16 : 15; }
 
-// Probes before a workgroup gives up waiting for its group (about 2 s; test hook: PKV_SPIN_LIMIT).
-static int resident_spin_limit() {
-  if (const char* e = getenv("PKV_SPIN_LIMIT")) return atoi(e);
-  return 1 << 20;
-}
+// Wall-clock bound of every wait between workgroups, in 10 ns ticks: 50 ms, several thousand times what a wait
+// takes when the grid is resident.
+constexpr int kResidentWaitTicks = 5000000;
 
 // lse_mode: with supplied denominators the workgroups of the persistent kernel never wait for each other, so it
 // runs on a device of any size.
-static bool use_resident(const Plan& plan, bool lse_mode) {
-  if (const char* e = getenv("PKV_SCORE_PATH")) {  // test hook: "stream" forces the per-layer kernels
-    if (!strcmp(e, "stream")) return false;
-  }
+static bool use_resident(const Plan& plan, bool lse_mode, int32_t flags) {
+  if (flags & PKV_FLAG_STREAM_SCORING) return false;
   return plan.resident_ok && (lse_mode || device_fits_resident());
 }
 
@@ -186,7 +174,7 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
   float* pooled_ws = reinterpret_cast<float*>(ws + plan.off_pooled);
   const float kappa = (float)(1.4426950408889634 / sqrt((double)d.d));
   const bool lse_mode = ptrs[0].lse != nullptr;  // all layers or none (checked by the caller)
-  const bool resident = use_resident(plan, lse_mode);
+  const bool resident = use_resident(plan, lse_mode, d.flags);
   bool any_scores = false;
   for (int32_t l = 0; l < L; ++l) any_scores = any_scores || descs[l].k_l < d.N;
   if (rec) rec->begin(stream);
@@ -216,17 +204,14 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       const int32_t all_words = (int32_t)((cbuf_off + (size_t)plan.ngroups * plan.UPG * plan.res_Rpad * sizeof(uint64_t)) / 4);
       ra.zero_base = l0 == 0 ? ra.err : ra.cnt;
       ra.sync_words = l0 == 0 ? all_words : all_words - 2;
-      ra.dbg = reinterpret_cast<long long*>(ws + plan.off_dbg);
       ra.L = nl; ra.B = d.B; ra.Hq = d.Hq; ra.Hkv = d.Hkv; ra.G = plan.G; ra.alpha = d.alpha; ra.N = d.N;
       ra.R = plan.R; ra.Rpad = plan.res_Rpad; ra.nrb = plan.res_nrb; ra.TPU = plan.TPU;
       ra.ngroups = plan.ngroups; ra.UPG = plan.UPG;
-      ra.stagger = resident_stagger(lse_mode ? 0 : 250);
-      ra.spin_limit = resident_spin_limit();
+      ra.stagger = lse_mode ? 0 : kResidentStagger;
+      ra.wait_ticks = (d.flags & PKV_FLAG_NO_WAIT) ? 0 : kResidentWaitTicks;
       // the tagged exchange (every part of a group takes part in every unit, also one that lies beyond the end of a
-      // shorter sequence) is worth it when a unit has enough parts to spread the rows over (test hook:
-      // PKV_FOLD=counter keeps the arrival counter)
-      const char* fold = getenv("PKV_FOLD");
-      ra.tagged = (!lse_mode && plan.TPU >= 16 && !(fold && !strcmp(fold, "counter"))) ? 1 : 0;
+      // shorter sequence) is worth it when a unit has enough parts to spread the rows over
+      ra.tagged = (!lse_mode && plan.TPU >= 16 && !(d.flags & PKV_FLAG_COUNTER_EXCHANGE)) ? 1 : 0;
       ra.part_words = (int32_t)((size_t)plan.ngroups * plan.UPG * plan.TPU * plan.res_Rpad * 2);
       ra.set1_w = resident_set1_weight(ra.tagged != 0);
       ra.d = d.d;
@@ -304,7 +289,6 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
     se.pool_w = d.pool_w;
     se.nrb = nrb;
     se.inv_G = resident ? 1.0f : 1.0f / (float)plan.G;
-    se.dbg = reinterpret_cast<long long*>(ws + plan.off_dbg) + kResidentGrid * 16 + 1024;
     // the error word of this call's scoring launches
     se.err = (any_scores && resident) ? reinterpret_cast<const int32_t*>(ws + plan.off_cnt) : nullptr;
     ga.L = nl; ga.B = d.B; ga.Hkv = d.Hkv; ga.d = d.d; ga.k_cap_max = k_cap_max; ga.N = d.N;
@@ -341,7 +325,7 @@ static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const vo
     if (rc != PKV_OK) return rc;
     const pkv_layer_desc &a = descs[0], &b = descs[l];
     if (a.B != b.B || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.N != b.N || a.alpha != b.alpha ||
-        a.pool != b.pool || a.pool_w != b.pool_w || a.q_sb != b.q_sb || a.q_sh != b.q_sh || a.q_st != b.q_st ||
+        a.pool != b.pool || a.pool_w != b.pool_w || a.flags != b.flags || a.q_sb != b.q_sb || a.q_sh != b.q_sh || a.q_st != b.q_st ||
         a.kv_sb != b.kv_sb || a.kv_sh != b.kv_sh || a.kv_st != b.kv_st)
       return PKV_ERR_INVALID_ARG;
     ptrs[l] = {Q_win[l], K[l], V[l], K_out[l], V_out[l], idx_out[l], count_out[l],
@@ -510,38 +494,33 @@ int pkv_decode_attention(const pkv_decode_desc* desc, const void* q, const void*
 int pkv_budgets_schedule(int32_t L, int32_t avg_budget, int32_t beta, int32_t alpha, int32_t schedule,
                          int32_t* k_out) {
   if (schedule == PKV_SCHEDULE_LINEAR) return pkv_budgets(L, avg_budget, beta, alpha, k_out);
-  if (L < 1 || beta < 1 || alpha < 0 || avg_budget < alpha || !k_out) return PKV_ERR_INVALID_ARG;
+  if (L < 1 || L > kMaxLayers || beta < 1 || alpha < 0 || avg_budget < alpha || !k_out) return PKV_ERR_INVALID_ARG;
   if (schedule != PKV_SCHEDULE_GEOMETRIC && schedule != PKV_SCHEDULE_UNIFORM) return PKV_ERR_INVALID_ARG;
-  if (schedule == PKV_SCHEDULE_UNIFORM || L == 1 || beta == 1) {
-    for (int32_t l = 0; l < L; ++l) k_out[l] = avg_budget;
-    return PKV_OK;
+  std::fill(k_out, k_out + L, avg_budget);
+  if (schedule == PKV_SCHEDULE_UNIFORM || L == 1 || beta == 1) return PKV_OK;
+  // Geometric decay over the budget left after the window: r_l = r_0 q^l.  The ratio of top to bottom layer is the
+  // linear pyramid's, q^(L-1) = 1/(2 beta - 1), and the layers share L * rest units, so by the closed form of the
+  // geometric series r_0 = L * rest * (1 - q) / (1 - q^L).  The values follow from r_0 by repeated multiplication.
+  const int64_t rest = (int64_t)avg_budget - alpha;
+  const double ln_ratio = -log(2.0 * beta - 1.0);
+  const double q = exp(ln_ratio / (L - 1));
+  const double qL = exp(ln_ratio * L / (L - 1));
+  struct Share { double frac; int32_t layer; };
+  std::vector<Share> share(L);
+  int64_t missing = (int64_t)L * rest;
+  double r = (double)L * (double)rest * (1.0 - q) / (1.0 - qL);
+  for (int32_t l = 0; l < L; ++l, r *= q) {
+    const double whole = floor(r);
+    k_out[l] = alpha + (int32_t)whole;
+    missing -= (int64_t)whole;
+    share[l] = {r - whole, l};
   }
-  // r_l = C q^l, q^(L-1) = 1 / (2 beta - 1) (the linear pyramid's ratio of top to bottom layer), sum_l r_l = L A
-  const double A = (double)(avg_budget - alpha);
-  const double q = pow(1.0 / (2.0 * (double)beta - 1.0), 1.0 / (double)(L - 1));
-  double frac[kMaxLayers];
-  if (L > kMaxLayers) return PKV_ERR_INVALID_ARG;
-  double sum = 0.0;
-  for (int32_t l = 0; l < L; ++l) {
-    frac[l] = pow(q, (double)l);
-    sum += frac[l];
-  }
-  int64_t given = 0;
-  for (int32_t l = 0; l < L; ++l) {
-    const double r = (double)L * A * frac[l] / sum;
-    k_out[l] = (int32_t)floor(r);
-    given += k_out[l];
-    frac[l] = r - floor(r);
-  }
-  // the missing units go, one each, to the largest fractional parts; equal parts: the lower layer first
-  for (int64_t left = (int64_t)L * (avg_budget - alpha) - given; left > 0; --left) {
-    int32_t best = 0;
-    for (int32_t l = 1; l < L; ++l)
-      if (frac[l] > frac[best]) best = l;
-    k_out[best] += 1;
-    frac[best] = -1.0;
-  }
-  for (int32_t l = 0; l < L; ++l) k_out[l] += alpha;
+  // Integer budgets as for the linear schedule: the units the floors leave over go, one each, to the layers with the
+  // largest fractional parts (equal parts: the lower layer first).  Rounding of the series can leave the count one
+  // off the number of layers at most; the clamp keeps the sum exact in any case.
+  std::stable_sort(share.begin(), share.end(), [](const Share& x, const Share& y) { return x.frac > y.frac; });
+  for (int64_t i = 0; i < missing; ++i) k_out[share[(size_t)(i % L)].layer] += 1;
+  for (int64_t i = 0; i > missing; --i) k_out[share[(size_t)(L - 1 + i % L)].layer] -= 1;
   return PKV_OK;
 }
 
@@ -554,7 +533,8 @@ int pkv_attention_recall(int32_t L, const pkv_layer_desc* descs, int32_t lse_sup
     const int rc = check_desc(&descs[l]);
     if (rc != PKV_OK) return rc;
     const pkv_layer_desc &a = descs[0], &b = descs[l];
-    if (a.B != b.B || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.N != b.N || a.alpha != b.alpha)
+    if (a.B != b.B || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.N != b.N || a.alpha != b.alpha ||
+        a.flags != b.flags)
       return PKV_ERR_INVALID_ARG;
     if (!idx_out[l] || !recall_out[l] || ((uintptr_t)idx_out[l] & 3) || ((uintptr_t)recall_out[l] & 3))
       return PKV_ERR_INVALID_ARG;
@@ -565,7 +545,7 @@ int pkv_attention_recall(int32_t L, const pkv_layer_desc* descs, int32_t lse_sup
   if (wrc != PKV_OK) return wrc;
   // where the compress call left the un-pooled scores: one array per layer (resident path, already divided by the
   // group size) or one partial per row block (streaming path)
-  const bool resident = use_resident(plan, lse_supplied != 0);
+  const bool resident = use_resident(plan, lse_supplied != 0, d.flags);
   const int nrb = resident ? 1 : plan.nrb;
   const float* raw = reinterpret_cast<const float*>(static_cast<const char*>(workspace) + plan.off_raw);
   for (int32_t l0 = 0; l0 < L; l0 += kBatchMaxLayers) {

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "pkv.h"
+#include "pkv_measure.h"
 
 namespace pkv {
 
@@ -39,7 +40,7 @@ struct Plan {
   int KC;        // keys per score workgroup (multiple of 128)
   int nchunk;    // ceil(N / KC)
   // workspace carve-up (byte offsets, each 256-aligned)
-  size_t off_cnt, off_part, off_cfin, off_raw, off_pooled, off_dbg, total;
+  size_t off_cnt, off_part, off_cfin, off_raw, off_pooled, total;
   size_t sync_bytes;  // error word + counters + tagged normalisers (zeroed before each resident launch)
 };
 
@@ -83,7 +84,6 @@ struct ResidentArgs {
   int32_t* err;   // in front of cnt: set to 1 if a bounded wait gave up; cleared by the first launch of a call only
   int32_t* zero_base;  // start of the words to zero before the launch (err or cnt)
   unsigned long long* cbuf;  // [nslots][Rpad] (unit tag << 32 | normaliser bits), behind err, 8-byte aligned
-  long long* dbg; // per-workgroup phase timers (development builds only), may be null
   int32_t sync_words;  // 32-bit words to zero from zero_base: (error word,) counters, cbuf
   int32_t L, B, Hq, Hkv, G, alpha, N, R, Rpad, nrb, TPU, U, d;
   int32_t ngroups;  // independent groups of workgroups: 512 / group size
@@ -93,7 +93,8 @@ struct ResidentArgs {
   int32_t set1_w;   // share (of 32) of a group pair's units that goes to the group of second workgroups
   int32_t stagger;  // start offset between consecutive groups, in 10 ns ticks
   int32_t lse_mode;    // 1: every layer carries lse; one sweep, no exchange between workgroups
-  int32_t spin_limit;  // probes of a tagged word before a workgroup gives up waiting and raises the error word
+  int32_t wait_ticks;  // wall-clock bound (10 ns ticks) of a wait for other workgroups; beyond it the workgroup
+                       // raises the error word and carries on (0: give up at once)
   int64_t q_sb, q_sh, q_st, kv_sb, kv_sh, kv_st;
   float kappa, inv_kappa, inv_G;
 };
@@ -117,7 +118,6 @@ struct SelectBatchArgs {
   int32_t B, Hkv, N, alpha, pool, pool_w;
   int32_t nrb;         // partial score arrays to add per layer
   float inv_G;         // factor applied to the sum of the partials
-  long long* dbg;      // per-unit phase timers (development builds only), may be null
   const int32_t* err;  // error word of the scoring kernel (non-zero: a wait was given up), or null
 };
 

@@ -40,8 +40,8 @@
 // a row tile whose sums leave a safe range is recomputed with the exact running-maximum update, and so
 // are tiles that touch the causal window or the end of the sequence (they need masks).
 //
-// Every wait is bounded: a workgroup that spins too long raises the error word and carries on, so the
-// grid always drains.  The launch uses exactly 512 workgroups, two per compute unit (register- and
+// Every wait is bounded by wall-clock time: a workgroup that has waited too long raises the error word and
+// carries on, so the grid always drains.  The launch uses exactly 512 workgroups, two per compute unit (register- and
 // LDS-limited), which the host checks against the device before choosing this path.
 //
 // One-sweep variant (second template argument): when the caller supplies the softmax denominators of the
@@ -117,9 +117,11 @@ __device__ __forceinline__ int fresh(int v) {
   return v;
 }
 
-// Workgroup barrier that orders LDS traffic only.  A full __syncthreads() also waits until every global store of
-// the wave has been acknowledged, and with it, since memory operations retire in order, for every key load that
-// was requested in between: exactly the loads that are meant to stay in flight across the barrier.
+// Workgroup barrier that orders LDS traffic only.  A full __syncthreads() carries fences over global memory as
+// well, and the waits the compiler builds for them include, since memory operations retire in order, every key
+// load requested before: exactly the loads that are meant to stay in flight across the barrier.  (Neither kind
+// of barrier waits for the acknowledgement of outstanding global stores: where another workgroup is told that
+// data is ready, the storing waves wait for vmcnt(0) themselves.)
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
@@ -189,21 +191,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   const int key0 = part_id * kResidentKeys;
   const int wkey0 = key0 + wave * (kTiles * 32);
 
-#ifdef PKV_RES_TIMING
-  long long tstamp[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  tstamp[5] = -(long long)clock64();
-  tstamp[6] = -(long long)wall_clock64();
-  // absolute phase-boundary times of one workgroup of every group: blocks 0,2,4,6 and 256,258,260,262
-  const int trace_id = ((blockIdx.x & ~0x106) == 0 && (blockIdx.x & 1) == 0) ? (int)((blockIdx.x >> 8) * 4 + ((blockIdx.x & 6) >> 1)) : -1;
-  int trace_n = 0;
-#define PKV_TRACE() do { if (trace_id >= 0 && trace_n < 128 && tid == 0 && a.dbg) a.dbg[kResidentGrid * 8 + trace_id * 128 + trace_n] = wall_clock64(); ++trace_n; } while (0)
-#define PKV_T(i) do { tstamp[i] += wall_clock64(); if (i != 0) PKV_TRACE(); } while (0)
-#define PKV_TN(i) do { tstamp[i] -= wall_clock64(); if (i == 1) PKV_TRACE(); } while (0)
-  if (set == 1 && a.stagger < 0) return;  // measurement: one workgroup per compute unit
-#else
-#define PKV_T(i)
-#define PKV_TN(i)
-#endif
 
   if (a.stagger > 0 && a.ngroups >= 2) {
     // Staggered start (a plain timed wait): the groups begin evenly spread over one period, the two
@@ -411,6 +398,20 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     }
   };
 
+  // Every wait for another workgroup is bounded by wall-clock time (the grid must drain even if its workgroups are
+  // not resident together).  Called after a failed probe: true once the wait has lasted wait_ticks (10 ns each)
+  // or another workgroup has already given up.  The clock is read every 16th probe (a probe is a memory round trip).
+  auto waited_too_long = [&](int& spins, long long& t0) -> bool {
+    if (a.wait_ticks == 0) return true;
+    if (spins++ == 0) {
+      t0 = wall_clock64();
+      return false;
+    }
+    if ((spins & 15) != 0) return false;
+    return wall_clock64() - t0 > (long long)a.wait_ticks ||
+           __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+  };
+
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   if (tid == 0) qsmem[SEG] = u32x4{0u, 0u, 0u, 0u};  // pad slot of row 0: never written by the staging
@@ -425,7 +426,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   }
   if (cur_u.u >= a.U) return;
   int buf = 0;
-  PKV_TN(0);
   if (LSE && tid < kRowBlock) {  // row offsets of block 0: the same for every unit
     int off = -1;
     if (tid < a.R) {
@@ -448,7 +448,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
   issue_k(cur_u, I2{}, I0{}, IKS{});
   issue_k(cur_u, I3{}, I0{}, IKS{});
   __syncthreads();
-  PKV_T(0);
 
   while (cur_u.u < a.U) {
     const int u = cur_u.u, n = cur_u.n, npre = cur_u.npre, nparts = cur_u.nparts;
@@ -474,7 +473,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
     auto q_frag = [&](int rt, int ks) { return as_frag(q_lane[32 * rt * PITCH + 2 * ks]); };
 
     if constexpr (!LSE) {
-    PKV_TN(1);
     // ---- sweep 1: per-row statistics over this workgroup's keys ----
     // Products: rows = keys (element v of a lane: key mrow0(v) + 4*hf of the tile), columns = query rows
     // (lane & 31).  Per lane and row tile: reference exponent m (log2 domain) and z = sum exp2(x - m), kept in
@@ -654,10 +652,15 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         st64(reinterpret_cast<u64*>(part + rb * kRowBlock + tid), ((u64)zb << 32) | __float_as_uint(m));
       }
     }
-    if (a.tagged) lds_barrier();  // (nobody waits for these stores: their readers look at the tag)
-    else __syncthreads();         // also waits for the stores above to be acknowledged
-    PKV_T(1);
-    PKV_TN(2);
+    if (a.tagged) {
+      lds_barrier();  // (nobody waits for these stores: their readers look at the tag)
+    } else {
+      // Release: the arrival below tells the last arriver that this part's statistics can be read, so every
+      // wave first waits until its own statistics stores have been acknowledged (a workgroup barrier alone
+      // does not wait for outstanding global stores), and only then does the workgroup meet.
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+      __syncthreads();
+    }
 
     // ---- arrive; the last part folds all parts into the per-row normaliser and publishes it ----
     // Tagged mode (every part takes part in every unit of its group): no counter and no last arriver.  Part p folds
@@ -672,12 +675,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         for (int p = lane; p < nparts; p += 64) {
           const u64* src = reinterpret_cast<const u64*>(part_base + (size_t)p * a.Rpad + r);
           int spins = 0;
+          long long t0 = 0;
           u64 w;
           for (;;) {
             w = ld64(src);
             if ((uint32_t)(w >> 63) == phase) break;
             __builtin_amdgcn_s_sleep(2);
-            if (++spins > a.spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+            if (waited_too_long(spins, t0)) {
               __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               break;
             }
@@ -700,10 +704,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       last = s_last != 0;
     }
     if (last) {
-#ifdef PKV_RES_TIMING
-      tstamp[3] -= wall_clock64();
-      tstamp[7] += 1;
-#endif
       // NQ threads per row, each folds every NQ-th part (32 independent loads in flight), then they meet in LDS
       constexpr int NQ = kThreads / kRowBlock;
       constexpr int NLD = 32;
@@ -745,9 +745,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         }
         lds_barrier();
       }
-#ifdef PKV_RES_TIMING
-      tstamp[3] += wall_clock64();
-#endif
       if (has_next) {  // before this unit's sweep 2 requests the next keys: loads return in order
         stage_q(nxt_u, 0, qsmem + (buf ^ 1) * QBUF);
         q_staged = true;
@@ -762,12 +759,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         float c = -INFINITY;
         if (r < a.R) {
           int spins = 0;
+          long long t0 = 0;
           u64 w;
           for (;;) {
             w = ld64(&cbuf[r]);
             if ((unsigned)(w >> 32) == tag) break;
             __builtin_amdgcn_s_sleep(1);
-            if (++spins > a.spin_limit || ((spins & 1023) == 0 && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+            if (waited_too_long(spins, t0)) {
               __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               break;
             }
@@ -779,9 +777,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       lds_barrier();
     }
     __builtin_amdgcn_s_setprio(0);
-    PKV_T(2);
     }  // !LSE
-    PKV_TN(4);
 
     // ---- sweep 2: normalised probabilities summed over the query rows ----
     // Here the product's rows are query rows (element v of a lane: row mrow0(v) + 4*hf of the tile) and its
@@ -891,14 +887,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
           issue_k(ru, F1, I0{}, IKS{});
         }
       };
-#ifdef PKV_RES_TIMING
-      if constexpr (LSE) {  // time spent waiting for the first half of the keys (the second half stays in flight)
-        PKV_TN(0);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * KS) & 15) | (((2 * KS) >> 4) << 14));
-        PKV_T(0);
-        PKV_TN(1);
-      }
-#endif
       // LSE: the next unit's denominators and Q block travel while this unit is computed: the denominators and one
       // half of the rows during the first pass, the other half during the second.  Each is written to the other
       // LDS buffers (read from the start of the next unit, behind the barrier that ends this one) at a place where
@@ -910,15 +898,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
       if (prefetch) lse_request(nxt_u, lv);
       if (prefetch_q) q_request(nxt_u, I0{}, qv);
       pass(I0{}, I1{}, std::false_type{}, I2{}, I3{}, cur_u);
-#ifdef PKV_RES_TIMING
-      if constexpr (LSE) {
-        PKV_T(1);
-        PKV_TN(2);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        PKV_T(2);
-        PKV_TN(3);
-      }
-#endif
       if (prefetch) lse_commit(lv, cfr_nxt);
       if (prefetch_q) q_commit(qv, I0{}, qsmem + (buf ^ 1) * QBUF);
       // The item after the next one is drawn here: every earlier request of the wave has just been waited for and
@@ -938,32 +917,19 @@ __global__ __launch_bounds__(kThreads, 2) void score_resident_kernel(const Resid
         issue_k(has_next ? nxt_u : cur_u, I2{}, I0{}, IKS{});
         issue_k(has_next ? nxt_u : cur_u, I3{}, I0{}, IKS{});
       }
-#ifdef PKV_RES_TIMING
-      if constexpr (LSE) PKV_T(3);
-#endif
     };
     for (int rb = 0; rb + 1 < a.nrb; ++rb) s2_block(rb, std::false_type{});
     s2_block(a.nrb - 1, std::true_type{});
     if (!LSE && has_next && !q_staged) stage_q(nxt_u, 0, qsmem + (buf ^ 1) * QBUF);
     if (LSE && tid < 2) s_item[tid == 0 ? buf : 3] = 2 * kResidentGrid + drawn;  // (lane 1: the spare word)
     lds_barrier();  // cfr / stat and the Q buffers change hands
-    PKV_T(4);
     cur_u = nxt_u;
     if constexpr (LSE) {
-#ifdef PKV_RES_TIMING
-      tstamp[7] += 1;
-#endif
       // (the word is written again two units from now, behind the next barrier: everyone has read it by then)
       if (has_next) take(s_item[buf], nxt_u);
     }
     buf ^= 1;
   }
-#ifdef PKV_RES_TIMING
-  tstamp[5] += clock64();
-  tstamp[6] += wall_clock64();
-  if (tid == 0 && a.dbg)
-    for (int i = 0; i < 8; ++i) a.dbg[blockIdx.x * 8 + i] = tstamp[i];
-#endif
 }
 
 // Clears n words at p and n2 words at p2 (p2 16-byte aligned, n2 a multiple of 4: four words per thread there).

@@ -1,5 +1,5 @@
-// Group mean, 1-D pooling and per-head top-k selection (Sec. 4.2.2: "a pooling layer", "the top k^l
-// tokens with the highest scores are selected"; the alpha instruction tokens are always kept).
+// Group mean, 1-D pooling and per-head top-k selection (Sec. 4.2.2: pooling of the window scores, then
+// the k^l - alpha highest-scoring prefix tokens per head; the alpha instruction tokens are always kept).
 //
 // One 1024-thread workgroup per unit (layer x sequence x KV head); all layers of a call run in one
 // launch.
@@ -32,8 +32,9 @@ constexpr int TL = 16384;          // pooling tile of long prefixes (outputs per
 constexpr int HIST = 2048;         // bins of the widest digit
 constexpr int kLdsKeys = 32768;    // prefix lengths up to this keep their keys in LDS
 
-// Workgroup barrier that orders LDS traffic only.  A full __syncthreads() also waits until every global load and
-// store of the wave has completed: a memory round trip per use, where only LDS contents change hands.
+// Workgroup barrier that orders LDS traffic only.  A full __syncthreads() carries fences over global memory too,
+// and the waits the compiler builds for them cover the global loads still in flight: a memory round trip per use,
+// where only LDS contents change hands.
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
@@ -77,19 +78,13 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* s
   return v + base;
 }
 
-#ifdef PKV_SEL_TIMING
-#define PKV_ST(i) do { if (threadIdx.x == 0 && blockIdx.x < 256 && g_dbg) g_dbg[blockIdx.x * 8 + i] = clock64(); } while (0)
-#else
-#define PKV_ST(i)
-#endif
 
 template <bool LDSKEYS>
 __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb_stride, float inv_G, float* pooled,
                                             bool write_pooled, int32_t* idx, int npre, int kk, int alpha, int pool,
                                             int pool_w, uint32_t* lkeys, uint32_t* hist,
-                                            uint32_t* scan32, uint32_t* sel, long long* g_dbg) {
+                                            uint32_t* scan32, uint32_t* sel) {
   const int tid = threadIdx.x;
-  PKV_ST(0);
   const int lane = tid & 63, wave = tid >> 6;
   const uint32_t* gkeys = reinterpret_cast<const uint32_t*>(pooled);
 
@@ -153,7 +148,6 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       }
     }
     __syncthreads();
-    PKV_ST(1);
     // window of half-width R around position i, summed (or maximised) in ascending position order.  A group of
     // 64 positions whose windows lie inside the prefix reads with constant offsets and no predicates.
     auto pool_fixed = [&](auto RR, auto MX) {
@@ -215,7 +209,6 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
     }
 #pragma unroll
     for (int j = 0; j < PER; ++j) rkeys[j] = (j < nval) ? __float_as_uint(v[j]) : 0u;
-    PKV_ST(2);
   } else {
     // Long prefix: tiles of TL outputs go through LDS, every load of a tile in flight at once; the pooled values
     // are the keys, kept in global memory.  On the way the largest and the smallest key are noted, and the largest
@@ -311,8 +304,6 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
       lds_barrier();  // (the tile is rewritten next; the pooled values are read only after the loop)
     }
     __syncthreads();  // the keys in global memory and the group maxima are complete
-    PKV_ST(1);
-    PKV_ST(2);
   }
 
   if (kk > 0) {
@@ -406,9 +397,6 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
           if (open) list[off++] = rkeys[j];
         }
         __syncthreads();
-#ifdef PKV_SEL_TIMING
-        if (threadIdx.x == 0 && blockIdx.x < 256 && g_dbg) { g_dbg[blockIdx.x * 8 + 5] = clock64(); g_dbg[blockIdx.x * 8 + 6] = bit; }
-#endif
         // ... and one wave finishes the search on them alone: 8 keys per lane, no barrier between the rounds
         if (wave == 0) {
           constexpr int LK = kList / 64;
@@ -488,9 +476,6 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
             }
           }
         }
-#ifdef PKV_SEL_TIMING
-        if (first_level) { __syncthreads(); PKV_ST(5); }
-#endif
         first_level = false;
         __syncthreads();
         // thread t owns bins 2t, 2t+1; suffix sums over the bins owned by higher threads
@@ -514,7 +499,6 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
         __syncthreads();
       }
     }
-    PKV_ST(3);
     const uint32_t T = prefix;           // bit pattern of the kk-th largest pooled score
 
     // ---- C. ordered emission ----
@@ -645,7 +629,6 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
     }
   }
   for (int t = tid; t < alpha; t += NT) idx[kk + t] = npre + t;
-  PKV_ST(4);
 }
 
 __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatchArgs a) {
@@ -682,10 +665,10 @@ __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatch
   float* pooled = ly.pooled + (size_t)bg * a.N;
   if (npre <= kLdsKeys)
     select_unit<true>(raw, a.nrb, rb_stride, a.inv_G, pooled, ly.write_pooled != 0, idx, npre, kk, a.alpha, a.pool,
-                      a.pool_w, lkeys, hist, scan32, sel, a.dbg);
+                      a.pool_w, lkeys, hist, scan32, sel);
   else
     select_unit<false>(raw, a.nrb, rb_stride, a.inv_G, pooled, true, idx, npre, kk, a.alpha, a.pool, a.pool_w,
-                       lkeys, hist, scan32, sel, a.dbg);
+                       lkeys, hist, scan32, sel);
 }
 
 }  // namespace

@@ -15,9 +15,12 @@ ROOT = os.path.dirname(HERE)
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "pkv.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(pkv_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in ("pkv.h", "pkv_measure.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(pkv_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_loads_and_exports_every_declared_symbol():
@@ -61,7 +64,7 @@ def test_budgets_reject_bad_arguments():
 
 
 def _desc(**kw):
-    base = dict(B=1, Hq=32, Hkv=8, d=128, N=4096, alpha=8, k_l=128, pool=1, pool_w=7, reserved=0,
+    base = dict(B=1, Hq=32, Hkv=8, d=128, N=4096, alpha=8, k_l=128, pool=1, pool_w=7, flags=0,
                 q_sb=32 * 8 * 128, q_sh=8 * 128, q_st=128, kv_sb=8 * 4096 * 128, kv_sh=4096 * 128, kv_st=128,
                 o_sb=8 * 128 * 128, o_sh=128 * 128, o_st=128)
     base.update(kw)
@@ -95,7 +98,7 @@ def test_compress_layer_rejects_bad_arguments_before_launching():
     assert _call(_desc(alpha=0, k_l=8)) == I
     assert _call(_desc(pool=7)) == I
     assert _call(_desc(pool_w=4)) == I
-    assert _call(_desc(reserved=1)) == I
+    assert _call(_desc(flags=8)) == I               # a bit outside PKV_FLAG_ALL
     assert _call(_desc(kv_st=130)) == I             # rows not 16-byte aligned
     assert _call(_desc(kv_st=64)) == I              # rows overlap
     assert _call(_desc(d=96, q_st=96, kv_st=96, o_st=96)) == U
@@ -168,7 +171,23 @@ def test_compress_layers_paged_rejects_inconsistent_paging():
     assert call(binding.PagedDesc(16, 64, 8, 0)) == binding.ERR_WORKSPACE   # valid so far
 
 
+def _geometric_fractions(L, avg, beta, alpha):
+    """Fractional parts of the real-valued geometric budgets, in 60-digit decimal arithmetic (test only)."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    q = (-(Decimal(2 * beta - 1).ln()) / (L - 1)).exp()
+    w = [q ** l for l in range(L)]
+    tot = sum(w)
+    r = [Decimal(L * (avg - alpha)) * x / tot for x in w]
+    return [x - int(x) for x in r]
+
+
 def test_budget_schedules_equal_oracle_on_a_grid():
+    # The library evaluates the geometric schedule its own way (closed-form first term, running product), the oracle
+    # with a power per layer; the integer budgets must agree, except that units may sit on other layers among layers
+    # whose fractional parts lie within 1e-9 of each other (the largest-remainder rule cannot tell them apart in
+    # double; e.g. L = 4, beta = 14 has q = 1/3 exactly and every fractional part equal to 1/2).
+    swaps = 0
     for sched in (pkv_oracle.SCHEDULE_LINEAR, pkv_oracle.SCHEDULE_GEOMETRIC, pkv_oracle.SCHEDULE_UNIFORM):
         for L in (1, 2, 3, 4, 7, 28, 32, 40, 80, 126):
             for avg in (64, 96, 128, 256, 512, 2048, 777):
@@ -177,7 +196,16 @@ def test_budget_schedules_equal_oracle_on_a_grid():
                         if avg < alpha:
                             continue
                         want = pkv_oracle.budgets_schedule(L, avg, beta, alpha, sched).tolist()
-                        assert binding.budgets_schedule(L, avg, beta, alpha, sched) == want, (sched, L, avg, beta, alpha)
+                        got = binding.budgets_schedule(L, avg, beta, alpha, sched)
+                        if got == want:
+                            continue
+                        assert sched == pkv_oracle.SCHEDULE_GEOMETRIC, (sched, L, avg, beta, alpha)
+                        diff = [(l, g - w) for l, (g, w) in enumerate(zip(got, want)) if g != w]
+                        assert all(abs(d) == 1 for _, d in diff) and sum(d for _, d in diff) == 0, (L, avg, beta, alpha, diff)
+                        fr = [_geometric_fractions(L, avg, beta, alpha)[l] for l, _ in diff]
+                        assert max(fr) - min(fr) < 1e-9, (L, avg, beta, alpha, diff)
+                        swaps += 1
+    assert swaps <= 5
     with pytest.raises(binding.PkvError):
         binding.budgets_schedule(4, 128, 20, 8, 9)
 

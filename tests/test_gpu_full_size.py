@@ -5,7 +5,8 @@ import pytest
 import torch
 
 from oracle import pkv_oracle
-from paper_2406_02069_amd import binding, prefill_stub, synth
+from paper_2406_02069_amd import binding, synth
+from tests import prefill_stub
 from tests.parity import compare_layer
 
 pytestmark = pytest.mark.gpu
@@ -75,7 +76,7 @@ def test_config3_mistral_ragged_batch():
 def test_config3_mistral_ragged_batch_with_the_arrival_counter(monkeypatch):
     # the exchange of softmax statistics through the arrival counter (the default for units of fewer than 16 parts)
     # at a size where the tagged exchange would be used
-    monkeypatch.setenv("PKV_FOLD", "counter")
+    monkeypatch.setattr(binding, "DESC_FLAGS", binding.FLAG_COUNTER_EXCHANGE)
     _full(3, 1)
 
 

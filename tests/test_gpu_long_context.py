@@ -7,7 +7,8 @@ import pytest
 import torch
 
 from oracle import pkv_oracle
-from paper_2406_02069_amd import binding, prefill_stub, synth
+from paper_2406_02069_amd import binding, synth
+from tests import prefill_stub
 from tests.parity import compare_layer
 
 pytestmark = pytest.mark.gpu

@@ -5,7 +5,8 @@ import pytest
 import torch
 
 from oracle import pkv_oracle
-from paper_2406_02069_amd import binding, prefill_stub, synth
+from paper_2406_02069_amd import binding, synth
+from tests import prefill_stub
 from tests.parity import compare_layer
 
 pytestmark = pytest.mark.gpu
@@ -14,7 +15,7 @@ DEV = "cuda:0"
 
 @pytest.fixture(params=["resident", "stream"])
 def score_path(request, monkeypatch):
-    monkeypatch.setenv("PKV_SCORE_PATH", request.param)
+    monkeypatch.setattr(binding, "DESC_FLAGS", binding.FLAG_STREAM_SCORING if request.param == "stream" else 0)
     return request.param
 
 
@@ -149,7 +150,7 @@ def _case(seed):
 @pytest.mark.parametrize("seed", range(30))
 @pytest.mark.parametrize("path", ["resident", "stream"])
 def test_random_shape(seed, path, monkeypatch):
-    monkeypatch.setenv("PKV_SCORE_PATH", path)
+    monkeypatch.setattr(binding, "DESC_FLAGS", binding.FLAG_STREAM_SCORING if path == "stream" else 0)
     d, Hkv, G, alpha, B, N, pool, pw, k_l, lens = _case(seed)
     print("lse case", seed, path, dict(d=d, Hkv=Hkv, G=G, alpha=alpha, B=B, N=N, pool=pool, pw=pw, k_l=k_l,
                                        lens=None if lens is None else lens.tolist()), flush=True)

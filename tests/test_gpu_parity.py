@@ -14,7 +14,7 @@ DEV = "cuda:0"
 @pytest.fixture(params=["resident", "stream"])
 def score_path(request, monkeypatch):
     """Both scoring implementations: K held in registers (default) and the per-layer streaming kernels."""
-    monkeypatch.setenv("PKV_SCORE_PATH", request.param)
+    monkeypatch.setattr(binding, "DESC_FLAGS", binding.FLAG_STREAM_SCORING if request.param == "stream" else 0)
     return request.param
 
 
@@ -249,21 +249,21 @@ def test_all_layers_without_score_output_keep_the_same_tokens():
 
 
 def test_given_up_wait_is_reported_through_the_counts(monkeypatch):
-    # Forced from the host: with a spin limit of zero every workgroup that has to wait for its group gives up at
+    # Forced from the host: with PKV_FLAG_NO_WAIT every workgroup that has to wait for its group gives up at
     # once.  The kernels still run to completion and stay in bounds; the caller sees count -1 and repeats the call.
-    monkeypatch.setenv("PKV_SCORE_PATH", "resident")
+    monkeypatch.setattr(binding, "DESC_FLAGS", 0)
     w = synth.WORKLOADS[2].scaled(N=5000, L=2)
     layers = [synth.make_layer(w, l, DEV) for l in range(w.L)]
     Qs, Ks, Vs = [x[0] for x in layers], [x[1] for x in layers], [x[2] for x in layers]
     ks = binding.budgets(w.L, 128, w.beta, w.alpha)
-    monkeypatch.setenv("PKV_SPIN_LIMIT", "0")
+    monkeypatch.setattr(binding, "DESC_FLAGS", binding.FLAG_NO_WAIT)
     bad = binding.compress_layers(Qs, Ks, Vs, ks, w.pool, w.pool_w)
     torch.cuda.synchronize()
     for out in bad:
         assert out[3].cpu().tolist() == [-1] * w.B
         idx = out[2].cpu().numpy()
         assert idx.min() >= 0 and idx.max() < w.N
-    monkeypatch.delenv("PKV_SPIN_LIMIT")
+    monkeypatch.setattr(binding, "DESC_FLAGS", 0)
     good = binding.compress_layers(Qs, Ks, Vs, ks, w.pool, w.pool_w, want_scores=True)
     torch.cuda.synchronize()
     for l, out in enumerate(good):

@@ -33,7 +33,7 @@ def _case(seed):
 @pytest.mark.parametrize("seed", range(60))
 @pytest.mark.parametrize("path", ["resident", "stream"])
 def test_random_shape(seed, path, monkeypatch):
-    monkeypatch.setenv("PKV_SCORE_PATH", path)
+    monkeypatch.setattr(binding, "DESC_FLAGS", binding.FLAG_STREAM_SCORING if path == "stream" else 0)
     d, Hkv, G, alpha, B, N, pool, pw, k_l, lens = _case(seed)
     print("case", seed, path, dict(d=d, Hkv=Hkv, G=G, alpha=alpha, B=B, N=N, pool=pool, pw=pw, k_l=k_l,
                                    lens=None if lens is None else lens.tolist()), flush=True)

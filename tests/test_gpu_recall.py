@@ -5,7 +5,8 @@ import pytest
 import torch
 
 from oracle import pkv_oracle
-from paper_2406_02069_amd import binding, prefill_stub, synth
+from paper_2406_02069_amd import binding, synth
+from tests import prefill_stub
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -50,7 +51,7 @@ def _check(Qs, Ks, Vs, k_ls, alpha, pool, pw, lens=None, use_lse=False):
 @pytest.mark.parametrize("path", ["resident", "stream"])
 @pytest.mark.parametrize("use_lse", [False, True])
 def test_recall_matches_the_definition(path, use_lse, monkeypatch):
-    monkeypatch.setenv("PKV_SCORE_PATH", path)
+    monkeypatch.setattr(binding, "DESC_FLAGS", binding.FLAG_STREAM_SCORING if path == "stream" else 0)
     alpha = 8
     Q, K, V = _rand(3, 8, 2, 128, 1300, alpha, seed=3, scale=2.0)
     lens = np.array([1300, 600, 5], dtype=np.int32)
@@ -62,7 +63,7 @@ def test_recall_matches_the_definition(path, use_lse, monkeypatch):
 
 @pytest.mark.parametrize("path", ["resident", "stream"])
 def test_recall_wide_groups_and_d64(path, monkeypatch):
-    monkeypatch.setenv("PKV_SCORE_PATH", path)
+    monkeypatch.setattr(binding, "DESC_FLAGS", binding.FLAG_STREAM_SCORING if path == "stream" else 0)
     for (d, Hq, Hkv, alpha, N) in [(64, 12, 4, 5, 900), (128, 64, 8, 32, 700), (64, 16, 2, 64, 500)]:
         print("recall geometry", path, d, Hq, Hkv, alpha, N, flush=True)
         Q, K, V = _rand(2, Hq, Hkv, d, N, alpha, seed=d + Hq)

@@ -23,37 +23,55 @@ def _sample_layers(w, k):
     return out[:k]
 
 
-def _full(cfg, n_layers, avg=None, lse=False):
-    """lse: through pkv_compress_layers_lse with the denominators a prefill attention kernel would supply,
-    against the oracle given the same fp32 values."""
+NEAR_TIES = dict(units=0, near_tie_units=0)   # over the whole module, printed by the last test
+
+
+def _full(cfg, n_layers, avgs=None, lse=False):
+    """All sampled layers in one pkv_compress_layers call per average budget, each compared with the oracle.
+    Several budgets: the scores of a layer do not depend on the budget, so the kept prefix sets must be nested.
+    lse: through pkv_compress_layers_lse with the denominators a prefill attention kernel would supply, against
+    the oracle given the same fp32 values."""
     w = synth.WORKLOADS[cfg]
-    avg = avg or w.avg_budgets[0]
-    ks = binding.budgets(w.L, avg, w.beta, w.alpha)
+    avgs = sorted(avgs or [w.avg_budgets[0]])
     sel = _sample_layers(w, n_layers)
     layers = [synth.make_layer(w, l, DEV) for l in sel]
     lens = layers[0][3]
     lens_dev = None if lens is None else torch.from_numpy(lens).to(DEV)
     Qs, Ks, Vs = [x[0] for x in layers], [x[1] for x in layers], [x[2] for x in layers]
-    if lse:
-        lses = [prefill_stub.window_lse(Q, K, lens) for Q, K in zip(Qs, Ks)]
-        outs = binding.compress_layers_lse(Qs, Ks, Vs, lses, [ks[l] for l in sel], w.pool, w.pool_w,
-                                           seq_lens=lens_dev, want_scores=True)
-    else:
-        outs = binding.compress_layers(Qs, Ks, Vs, [ks[l] for l in sel], w.pool, w.pool_w, seq_lens=lens_dev,
-                                       want_scores=True)
-    torch.cuda.synchronize()
+    lses = [prefill_stub.window_lse(Q, K, lens) for Q, K in zip(Qs, Ks)] if lse else None
     tot = dict(units=0, near_tie_units=0)
-    for i, ((Q, K, V, _), l, out) in enumerate(zip(layers, sel, outs)):
-        print(f"config {cfg} layer {l} k_l {ks[l]} lse {lse}: oracle ...", flush=True)
-        ref = None
+    prev = None
+    for avg in avgs:
+        ks = binding.budgets(w.L, avg, w.beta, w.alpha)
         if lse:
-            ref = pkv_oracle.compress_layer(Q, K, V, ks[l], w.alpha, w.pool, w.pool_w, seq_lens=lens,
-                                            lse=np.nan_to_num(lses[i].cpu().numpy(), nan=0.0))
-        st = compare_layer(Q, K, V, ks[l], w.alpha, w.pool, w.pool_w, lens, out, ref=ref)
-        print("   ", st, flush=True)
-        tot["units"] += st["units"]
-        tot["near_tie_units"] += st["near_tie_units"]
+            outs = binding.compress_layers_lse(Qs, Ks, Vs, lses, [ks[l] for l in sel], w.pool, w.pool_w,
+                                               seq_lens=lens_dev, want_scores=True)
+        else:
+            outs = binding.compress_layers(Qs, Ks, Vs, [ks[l] for l in sel], w.pool, w.pool_w, seq_lens=lens_dev,
+                                           want_scores=True)
+        torch.cuda.synchronize()
+        for i, ((Q, K, V, _), l, out) in enumerate(zip(layers, sel, outs)):
+            print(f"config {cfg} avg {avg} layer {l} k_l {ks[l]} lse {lse}: oracle ...", flush=True)
+            ref = None
+            if lse:
+                ref = pkv_oracle.compress_layer(Q, K, V, ks[l], w.alpha, w.pool, w.pool_w, seq_lens=lens,
+                                                lse=np.nan_to_num(lses[i].cpu().numpy(), nan=0.0))
+            st = compare_layer(Q, K, V, ks[l], w.alpha, w.pool, w.pool_w, lens, out, ref=ref)
+            print("   ", st, flush=True)
+            tot["units"] += st["units"]
+            tot["near_tie_units"] += st["near_tie_units"]
+        if prev is not None:   # nesting across the budget sweep (same scores, larger budget)
+            for l, small, large in zip(sel, prev[1], outs):
+                ka, kb = prev[0][l] - w.alpha, ks[l] - w.alpha
+                assert ka <= kb
+                a_idx, b_idx = small[2].cpu().numpy(), large[2].cpu().numpy()
+                for b in range(w.B):
+                    for g in range(w.Hkv):
+                        assert np.isin(a_idx[b, g, :ka], b_idx[b, g, :kb]).all(), (cfg, avg, l, b, g)
+        prev = (ks, outs)
     assert tot["near_tie_units"] <= max(1, tot["units"] // 10)
+    for k in tot:
+        NEAR_TIES[k] += tot[k]
     return tot
 
 
@@ -61,16 +79,13 @@ def test_config1_llama3_8b_8k():
     _full(1, 4)
 
 
-def test_config2_llama3_8b_32k_avg128():
-    _full(2, 2)
-
-
-def test_config2_llama3_8b_32k_avg2048():
-    _full(2, 1, avg=2048)
+def test_config2_llama3_8b_32k_all_four_budgets():
+    # the config's sweep of average budgets, layers first / last / middle / one seeded-random
+    _full(2, 4, avgs=[64, 128, 512, 2048])
 
 
 def test_config3_mistral_ragged_batch():
-    _full(3, 1)
+    _full(3, 4)
 
 
 def test_config3_mistral_ragged_batch_with_the_arrival_counter(monkeypatch):
@@ -81,7 +96,7 @@ def test_config3_mistral_ragged_batch_with_the_arrival_counter(monkeypatch):
 
 
 def test_config4_llama3_70b_32k():
-    _full(4, 1)
+    _full(4, 4)
 
 
 def test_config2_llama3_8b_32k_supplied_denominators():
@@ -94,3 +109,10 @@ def test_config3_mistral_ragged_batch_supplied_denominators():
 
 def test_config4_llama3_70b_32k_supplied_denominators():
     _full(4, 1, lse=True)
+
+
+def test_zz_near_ties_over_the_module():
+    # reported for the record; near-ties (two distinct oracle values within 1e-5 of the cut) must stay rare
+    print("near-tie units over the full-size cases:", NEAR_TIES, flush=True)
+    assert NEAR_TIES["units"] > 0
+    assert NEAR_TIES["near_tie_units"] <= max(2, NEAR_TIES["units"] // 50)

@@ -26,7 +26,8 @@
  *  - Inputs are never modified.
  *  - The library keeps no state between calls and reads no environment
  *    variables.  (The per-device attributes of its kernels are set on first
- *    use.)
+ *    use; pkv_compress_layer_noalloc has a built-in scratch buffer per device,
+ *    see there.)
  *  - Exclusive use of the device.  Whenever a device with at least 256
  *    compute units is given a shape the register-resident scoring kernel
  *    serves (G*alpha <= 512, N <= 262144) without supplied softmax
@@ -58,7 +59,9 @@ typedef enum {
   PKV_ERR_INVALID_ARG = 1, /* NULL pointer, bad size, bad stride, bad enum   */
   PKV_ERR_UNSUPPORTED = 2, /* valid in the paper's terms, not built here     */
   PKV_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned or too small        */
-  PKV_ERR_HIP = 4          /* a kernel launch was rejected by the runtime    */
+  PKV_ERR_HIP = 4,         /* a kernel launch was rejected by the runtime    */
+  PKV_ERR_SCRATCH = 5      /* shape needs more than the built-in scratch
+                              buffer of pkv_compress_layer_noalloc holds     */
 } pkv_status;
 
 typedef enum {
@@ -199,6 +202,32 @@ int pkv_compress_layer(const pkv_layer_desc* desc, const void* Q_win,
                        void* K_out, void* V_out, int32_t* idx_out,
                        int32_t* count_out, float* scores_out, void* workspace,
                        size_t workspace_bytes, void* stream);
+
+/*
+ * pkv_compress_layer for callers that cannot hand over a workspace and must
+ * not cause an allocation: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * pkv_compress_layer, without the workspace: the kernels use a scratch
+ * buffer of PKV_NOALLOC_SCRATCH_BYTES that is part of the library's device
+ * image (every device the library runs on holds one until the process ends).
+ * The call allocates and frees nothing, on the host or on the device.
+ *
+ * A shape whose pkv_workspace_bytes(desc, 1) exceeds
+ * PKV_NOALLOC_SCRATCH_BYTES -> PKV_ERR_SCRATCH, nothing launched.  (32 MiB
+ * serve, e.g., B*Hkv = 8 heads of 262144 keys, or 64 heads of 32768.)
+ * All calls on one device share that device's buffer: calls that may overlap
+ * in time on one device race and give undefined results; serialise them (one
+ * stream, or events).  The buffer keeps the last call's contents; the call
+ * clears what it needs cleared itself.
+ */
+#define PKV_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+
+int pkv_compress_layer_noalloc(const pkv_layer_desc* desc, const void* Q_win,
+                               const void* K, const void* V,
+                               const int32_t* seq_lens, void* K_out,
+                               void* V_out, int32_t* idx_out,
+                               int32_t* count_out, float* scores_out,
+                               void* stream);
 
 /*
  * Compress L layers of one request batch (the whole prefill-time step: every

@@ -17,14 +17,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpkv.so")
 
 POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_SCRATCH = 0, 1, 2, 3, 4, 5
+NOALLOC_SCRATCH_BYTES = 32 << 20   # PKV_NOALLOC_SCRATCH_BYTES of include/pkv.h
 
 # pkv_layer_desc.flags (include/pkv_measure.h): test and measurement switches, 0 in production.  Descriptors made
 # by this module carry DESC_FLAGS, which tests set to run the other scoring path or exchange.
 FLAG_STREAM_SCORING, FLAG_COUNTER_EXCHANGE, FLAG_NO_WAIT = 1, 2, 4
 DESC_FLAGS = 0
 
-EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layers",
+EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layer_noalloc", "pkv_compress_layers",
            "pkv_compress_layers_lse", "pkv_compress_layers_paged", "pkv_compress_layers_profiled",
            "pkv_budgets_schedule", "pkv_attention_recall", "pkv_decode_attention", "pkv_decode_workspace_bytes", "pkv_probe_read", "pkv_status_string"]
 
@@ -69,6 +70,8 @@ def load() -> ctypes.CDLL:
         lib.pkv_workspace_bytes.restype = ctypes.c_size_t
         lib.pkv_compress_layer.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 10 + [ctypes.c_size_t, vp]
         lib.pkv_compress_layer.restype = ctypes.c_int
+        lib.pkv_compress_layer_noalloc.argtypes = [ctypes.POINTER(LayerDesc)] + [vp] * 10
+        lib.pkv_compress_layer_noalloc.restype = ctypes.c_int
         lib.pkv_compress_layers.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 10 + [ctypes.c_size_t, vp]
         lib.pkv_compress_layers.restype = ctypes.c_int
         lib.pkv_compress_layers_lse.argtypes = [i32, ctypes.POINTER(LayerDesc)] + [vp] * 11 + [ctypes.c_size_t, vp]
@@ -186,6 +189,24 @@ def compress_layer(Q_win: torch.Tensor, K: torch.Tensor, V: torch.Tensor, k_l: i
                                    _stream_ptr(K.device))
     if rc != OK:
         raise PkvError(rc, "pkv_compress_layer")
+    return outputs
+
+
+def compress_layer_noalloc(Q_win: torch.Tensor, K: torch.Tensor, V: torch.Tensor, k_l: int, pool: int, pool_w: int,
+                           outputs, seq_lens: Optional[torch.Tensor] = None):
+    """pkv_compress_layer_noalloc on the current torch stream: the library's built-in scratch buffer serves as the
+    workspace, and nothing is allocated here either (the caller passes the output tensors of alloc_outputs)."""
+    _check_bf16(Q_win, "Q_win"), _check_bf16(K, "K"), _check_bf16(V, "V")
+    if V.shape != K.shape or V.stride() != K.stride():
+        raise ValueError("K and V must have the same shape and strides")
+    K_out, V_out, idx, count, scores = outputs
+    desc = make_desc(Q_win, K, k_l, pool, pool_w, K_out)
+    if seq_lens is not None and (seq_lens.dtype != torch.int32 or not seq_lens.is_contiguous()):
+        raise ValueError("seq_lens must be a contiguous int32 tensor")
+    rc = load().pkv_compress_layer_noalloc(ctypes.byref(desc), _p(Q_win), _p(K), _p(V), _p(seq_lens), _p(K_out),
+                                           _p(V_out), _p(idx), _p(count), _p(scores), _stream_ptr(K.device))
+    if rc != OK:
+        raise PkvError(rc, "pkv_compress_layer_noalloc")
     return outputs
 
 

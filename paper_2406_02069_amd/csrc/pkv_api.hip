@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <vector>
 
 #include "pkv_internal.h"
@@ -350,6 +351,24 @@ static int compress_layers_impl(int32_t L, const pkv_layer_desc* descs, const vo
   return run_layers(L, descs, plan, ptrs, seq_lens, workspace, static_cast<hipStream_t>(stream), rec, paged);
 }
 
+// Built-in scratch buffer of pkv_compress_layer_noalloc: part of the device image, so every device the library
+// runs on holds its own copy at its own address until the process ends.  In host code the array's name is only a
+// stand-in for the symbol; the device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[PKV_NOALLOC_SCRATCH_BYTES];
+
+static int noalloc_scratch(void** out) {
+  static std::atomic<void*> device_ptr[kMaxDevices];
+  const int dev = current_device_slot();
+  if (dev < 0) return PKV_ERR_HIP;
+  void* p = device_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {  // first call on this device (which is current); two racing first calls find the same address
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PKV_ERR_HIP;
+    device_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return PKV_OK;
+}
+
 }  // namespace pkv
 
 using namespace pkv;
@@ -403,6 +422,20 @@ int pkv_compress_layer(const pkv_layer_desc* desc, const void* Q_win, const void
   float* const* so = scores_out ? &scores_out : nullptr;
   return compress_layers_impl(1, desc, &Q_win, &K, &V, seq_lens, &K_out, &V_out, &idx_out, &count_out, so,
                               workspace, workspace_bytes, stream, nullptr);
+}
+
+int pkv_compress_layer_noalloc(const pkv_layer_desc* desc, const void* Q_win, const void* K, const void* V,
+                               const int32_t* seq_lens, void* K_out, void* V_out, int32_t* idx_out,
+                               int32_t* count_out, float* scores_out, void* stream) {
+  const int drc = check_desc(desc);
+  if (drc != PKV_OK) return drc;
+  if (make_plan(*desc, 1).total > PKV_NOALLOC_SCRATCH_BYTES) return PKV_ERR_SCRATCH;
+  void* ws = nullptr;
+  const int src = noalloc_scratch(&ws);
+  if (src != PKV_OK) return src;
+  float* const* so = scores_out ? &scores_out : nullptr;
+  return compress_layers_impl(1, desc, &Q_win, &K, &V, seq_lens, &K_out, &V_out, &idx_out, &count_out, so, ws,
+                              PKV_NOALLOC_SCRATCH_BYTES, stream, nullptr);
 }
 
 int pkv_compress_layers(int32_t L, const pkv_layer_desc* descs, const void* const* Q_win, const void* const* K,
@@ -596,6 +629,7 @@ const char* pkv_status_string(int status) {
     case PKV_ERR_UNSUPPORTED: return "unsupported shape";
     case PKV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case PKV_ERR_HIP: return "HIP launch failed";
+    case PKV_ERR_SCRATCH: return "shape needs more scratch than the built-in buffer holds";
     default: return "unknown status";
   }
 }

@@ -33,7 +33,7 @@ def test_library_loads_and_exports_every_declared_symbol():
 
 def test_status_strings():
     assert binding.status_string(0) == "ok"
-    for s in range(1, 5):
+    for s in range(1, 6):
         assert binding.status_string(s) not in ("ok", "unknown status")
     assert binding.status_string(99) == "unknown status"
 
@@ -208,6 +208,24 @@ def test_budget_schedules_equal_oracle_on_a_grid():
     assert swaps <= 5
     with pytest.raises(binding.PkvError):
         binding.budgets_schedule(4, 128, 20, 8, 9)
+
+
+def test_noalloc_entry_point_checks_its_arguments_and_the_scratch_limit():
+    lib = binding.load()
+
+    def call(desc, Q=0x1000):
+        return lib.pkv_compress_layer_noalloc(ctypes.byref(desc), Q, 0x2000, 0x3000, None, 0x4000, 0x5000, 0x6000,
+                                              0x7000, None, None)
+
+    assert call(_desc(Hq=30)) == binding.ERR_INVALID_ARG
+    assert call(_desc(d=96, q_st=96, kv_st=96, o_st=96)) == binding.ERR_UNSUPPORTED
+    # 64 heads of 65536 keys need more scratch than the built-in buffer holds: refused before anything else happens
+    big = _desc(B=8, N=65536, kv_sh=65536 * 128, kv_sb=8 * 65536 * 128)
+    assert binding.workspace_bytes(big) > binding.NOALLOC_SCRATCH_BYTES
+    assert call(big) == binding.ERR_SCRATCH
+    assert binding.workspace_bytes(_desc()) <= binding.NOALLOC_SCRATCH_BYTES
+    text = open(os.path.join(ROOT, "include", "pkv.h")).read()
+    assert re.search(r"#define PKV_NOALLOC_SCRATCH_BYTES \(\(size_t\)32 << 20\)", text)
 
 
 def test_attention_recall_rejects_bad_arguments():

@@ -254,7 +254,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="index into the workload list (default: the 32k config)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="index into the workload list (default: the 32k config; 5: the multi-head long-context "
+                         "measurement shape)")
     ap.add_argument("--avg-budget", type=int, default=None)
     ap.add_argument("--seq-len", type=int, default=None,
                     help="variant: the same workload at another context length (e.g. 131072); no cpu_baseline")
@@ -283,7 +285,7 @@ def main():
     from paper_2406_02069_amd import binding, synth
 
     dev = "cuda:0"
-    w = synth.WORKLOADS[args.config]
+    w = (synth.WORKLOADS + synth.EXTRA_WORKLOADS)[args.config]
     if args.seq_len is not None and args.seq_len != w.N:
         w = w.scaled(name=f"{w.name}@N{args.seq_len}", N=args.seq_len)
     else:
@@ -383,14 +385,15 @@ def main():
 
     if not args.no_all_configs:
         # The other workloads of the configuration list, each measured the same way in a short run (they are
-        # parity-test cases; the headline stays the line above).
+        # parity-test cases; the headline stays the line above), and the multi-head long-context shape (8 query
+        # rows per head: what the padding of the rows to an MFMA tile costs per key).
         del call, Qs, Ks, Vs, lses, paged
         ctx.clear()
         gc.collect()
         torch.cuda.empty_cache()
         out["all_configs"] = []
-        for ci in (0, 1, 3, 4):
-            wc = synth.WORKLOADS[ci]
+        for ci in (0, 1, 3, 4, 5):
+            wc = (synth.WORKLOADS + synth.EXTRA_WORKLOADS)[ci]
             r, c = measure(wc, wc.avg_budgets[0], 10, 5, dev, want_read_probe=False)
             out["all_configs"].append({"config": r["config"]["workload"], "ms_per_step": r["ms_per_step"],
                                        "value": r["value"], "unit": "tokens/s",

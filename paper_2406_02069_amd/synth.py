@@ -66,6 +66,15 @@ WORKLOADS: List[Workload] = [
 ]
 
 
+# Beside the five configurations above: multi-head attention (G = 1, so only alpha = 8 query rows share a head's keys)
+# at a long context, the shape on which padding the query rows to a 32-row MFMA tile wastes the most exponentials.
+# A measurement shape (bench.py --config 5), not one of the parity configurations.
+EXTRA_WORKLOADS: List[Workload] = [
+    Workload("mha-32k", 5, B=1, L=8, Hq=32, Hkv=32, d=128, N=32768, alpha=8, avg_budgets=(128,), beta=20,
+             pool=POOL_MAX, pool_w=7, sink=True, needles=16),
+]
+
+
 def _seed(w: Workload, layer: int, stream: int) -> int:
     return (BASE_SEED + w.index) * 1_000_003 + layer * 101 + stream
 

@@ -31,7 +31,7 @@ def _full(cfg, n_layers, avgs=None, lse=False):
     Several budgets: the scores of a layer do not depend on the budget, so the kept prefix sets must be nested.
     lse: through pkv_compress_layers_lse with the denominators a prefill attention kernel would supply, against
     the oracle given the same fp32 values."""
-    w = synth.WORKLOADS[cfg]
+    w = (synth.WORKLOADS + synth.EXTRA_WORKLOADS)[cfg]
     avgs = sorted(avgs or [w.avg_budgets[0]])
     sel = _sample_layers(w, n_layers)
     layers = [synth.make_layer(w, l, DEV) for l in sel]
@@ -97,6 +97,11 @@ def test_config3_mistral_ragged_batch_with_the_arrival_counter(monkeypatch):
 
 def test_config4_llama3_70b_32k():
     _full(4, 4)
+
+
+def test_multi_head_32k_eight_query_rows_per_head():
+    # the measurement shape bench.py reports beside the five configurations: G = 1, 8 query rows padded to a tile
+    _full(5, 2)
 
 
 def test_config2_llama3_8b_32k_supplied_denominators():

@@ -79,7 +79,10 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* s
 }
 
 
-template <bool LDSKEYS>
+// PERT (prefix in LDS only): positions per thread, 1024 * PERT >= npre.  A short prefix is spread over all waves
+// (8 or 16 positions per thread) instead of filling the first few waves with 32 positions per thread and leaving
+// the others without keys: the rounds of the threshold search cost what the busiest wave needs.
+template <bool LDSKEYS, int PERT>
 __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb_stride, float inv_G, float* pooled,
                                             bool write_pooled, int32_t* idx, int npre, int kk, int alpha, int pool,
                                             int pool_w, uint32_t* lkeys, uint32_t* hist,
@@ -89,8 +92,8 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
   const uint32_t* gkeys = reinterpret_cast<const uint32_t*>(pooled);
 
   // ---- A. group mean + pooling ----
-  constexpr int PER = kLdsKeys / NT;   // positions per thread when the prefix lives in LDS
-  constexpr int CW = kLdsKeys / NW;    // ... and per wave: wave w owns positions [w * CW, (w + 1) * CW)
+  constexpr int PER = PERT;            // positions per thread when the prefix lives in LDS
+  constexpr int CW = 64 * PER;         // ... and per wave: wave w owns positions [w * CW, (w + 1) * CW)
   uint32_t rkeys[PER];                 // pooled keys of positions wave * CW + 64 * j + lane (0: no such position)
   const int r = (pool == PKV_POOL_NONE) ? 0 : (pool_w - 1) / 2;
   const bool is_max = pool == PKV_POOL_MAX;
@@ -98,7 +101,7 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
   const int pos0 = wave * CW + lane;   // the thread's first position; the others follow in steps of 64
   // number of the thread's positions that exist (position pos0 + 64 * j exists iff j < nval): one register instead
   // of 32 position registers kept alive for the comparisons
-  const int nval = min(max((npre - pos0 + 63) >> 6, 0), kLdsKeys / NT);
+  const int nval = min(max((npre - pos0 + 63) >> 6, 0), PER);
   uint32_t gmax = 0u, gmin = 0xFFFFFFFFu;  // long prefixes: largest and smallest key this thread has produced
   // long prefixes: largest key of every group of 64 positions, in LDS behind the pooling tile (if they fit)
   constexpr int kGrpOff = 16512, kGrpCap = kLdsKeys - kGrpOff;
@@ -663,12 +666,18 @@ __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatch
   const size_t rb_stride = (size_t)BH * a.N;
   const float* raw = a.raw + ((size_t)l * a.nrb * BH + bg) * a.N;
   float* pooled = ly.pooled + (size_t)bg * a.N;
-  if (npre <= kLdsKeys)
-    select_unit<true>(raw, a.nrb, rb_stride, a.inv_G, pooled, ly.write_pooled != 0, idx, npre, kk, a.alpha, a.pool,
-                      a.pool_w, lkeys, hist, scan32, sel);
+  if (npre <= 8 * NT)
+    select_unit<true, 8>(raw, a.nrb, rb_stride, a.inv_G, pooled, ly.write_pooled != 0, idx, npre, kk, a.alpha, a.pool,
+                         a.pool_w, lkeys, hist, scan32, sel);
+  else if (npre <= 16 * NT)
+    select_unit<true, 16>(raw, a.nrb, rb_stride, a.inv_G, pooled, ly.write_pooled != 0, idx, npre, kk, a.alpha,
+                          a.pool, a.pool_w, lkeys, hist, scan32, sel);
+  else if (npre <= kLdsKeys)
+    select_unit<true, kLdsKeys / NT>(raw, a.nrb, rb_stride, a.inv_G, pooled, ly.write_pooled != 0, idx, npre, kk,
+                                     a.alpha, a.pool, a.pool_w, lkeys, hist, scan32, sel);
   else
-    select_unit<false>(raw, a.nrb, rb_stride, a.inv_G, pooled, true, idx, npre, kk, a.alpha, a.pool, a.pool_w,
-                       lkeys, hist, scan32, sel);
+    select_unit<false, kLdsKeys / NT>(raw, a.nrb, rb_stride, a.inv_G, pooled, true, idx, npre, kk, a.alpha, a.pool,
+                                      a.pool_w, lkeys, hist, scan32, sel);
 }
 
 }  // namespace

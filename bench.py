@@ -275,7 +275,8 @@ def main():
                          "the time of the recall kernel; outside the timed region")
     ap.add_argument("--decode", action="store_true",
                     help="also time the step after the path: one decoding query per sequence attending over every "
-                         "layer's compacted cache (pkv_decode_attention, one launch per layer); outside the timed region")
+                         "layer's compacted cache (pkv_decode_attention, one launch per layer, and "
+                         "pkv_decode_attention_layers, one call for all layers); outside the timed region")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -360,6 +361,23 @@ def main():
                                    "algorithmic_bytes_per_step": dbytes,
                                    "achieved_GBps": dbytes / (dms * 1e-3) / 1e9,
                                    "frac_of_hbm_peak": dbytes / (dms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        # the same step through one call over all layers' caches (pkv_decode_attention_layers)
+        if paged is not None:
+            lc = binding.DecodeLayersCall(qd, [o[0] for o in outs], [o[1] for o in outs], [o[3] for o in outs],
+                                          block_tables=list(paged[2]), k_caps=[min(k, w.N) for k in ks])
+        else:
+            lc = binding.DecodeLayersCall(qd, [o[0] for o in outs], [o[1] for o in outs], [o[3] for o in outs])
+        for _ in range(20):
+            lc.run()
+        e0.record()
+        for _ in range(args.steps):
+            lc.run()
+        e1.record()
+        torch.cuda.synchronize()
+        lms = e0.elapsed_time(e1) / args.steps
+        out["decode_attention_layers"] = {"ms_per_step": lms, "calls": 1, "algorithmic_bytes_per_step": dbytes,
+                                          "achieved_GBps": dbytes / (lms * 1e-3) / 1e9,
+                                          "frac_of_hbm_peak": dbytes / (lms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
     if args.recall:
         rec = {}
         for name, sched in (("linear", binding.SCHEDULE_LINEAR), ("geometric", binding.SCHEDULE_GEOMETRIC),

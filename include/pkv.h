@@ -414,6 +414,43 @@ int pkv_decode_attention(const pkv_decode_desc* desc, const void* q,
                          float* out, float* lse_out, void* workspace,
                          size_t workspace_bytes, void* stream);
 
+/*
+ * pkv_decode_attention over the caches of L layers in one call (Sec. 3; the
+ * per-layer budgets of Sec. 4.2.1 make the layers' caches unequal and, at
+ * small batch, small: a launch per layer costs more than the rows it reads).
+ * For callers that hold the queries of several layers at once; a decoder
+ * that computes layer l+1's query from layer l's output calls
+ * pkv_decode_attention per layer.
+ *   descs[l]  HOST, L descriptors.  B, Hq, Hkv, d and page_size must be the
+ *             same for all layers; k_cap, num_pages, max_pages and the c_*
+ *             strides are per layer.
+ *   q, K_cache, V_cache, block_tables, count, out, lse_out
+ *             HOST arrays of L DEVICE pointers, each as in
+ *             pkv_decode_attention.  block_tables may be NULL for compact
+ *             caches; lse_out may be NULL (no log-sum-exp output), else all
+ *             L entries are written through.
+ *   workspace DEVICE, 256-byte aligned,
+ *             >= pkv_decode_layers_workspace_bytes(L, descs) bytes (may be
+ *             NULL when that is 0); contents irrelevant on entry, undefined
+ *             on exit; concurrent calls need distinct ones.
+ * Every layer's result is what pkv_decode_attention gives for it, up to the
+ * order of the fp32 additions (the key ranges are cut differently).
+ * Asynchronous on `stream`, never allocates.  Errors as for
+ * pkv_decode_attention; layers that differ in B, Hq, Hkv, d or page_size ->
+ * PKV_ERR_INVALID_ARG.
+ */
+size_t pkv_decode_layers_workspace_bytes(int32_t L,
+                                         const pkv_decode_desc* descs);
+int pkv_decode_attention_layers(int32_t L, const pkv_decode_desc* descs,
+                                const void* const* q,
+                                const void* const* K_cache,
+                                const void* const* V_cache,
+                                const int32_t* const* block_tables,
+                                const int32_t* const* count,
+                                float* const* out, float* const* lse_out,
+                                void* workspace, size_t workspace_bytes,
+                                void* stream);
+
 /* Static, NUL-terminated description of a pkv_status value.  HOST only. */
 const char* pkv_status_string(int status);
 

@@ -27,7 +27,8 @@ DESC_FLAGS = 0
 
 EXPORTS = ["pkv_budgets", "pkv_workspace_bytes", "pkv_compress_layer", "pkv_compress_layer_noalloc", "pkv_compress_layers",
            "pkv_compress_layers_lse", "pkv_compress_layers_paged", "pkv_compress_layers_profiled",
-           "pkv_budgets_schedule", "pkv_attention_recall", "pkv_decode_attention", "pkv_decode_workspace_bytes", "pkv_probe_read", "pkv_status_string"]
+           "pkv_budgets_schedule", "pkv_attention_recall", "pkv_decode_attention", "pkv_decode_workspace_bytes", "pkv_decode_attention_layers",
+           "pkv_decode_layers_workspace_bytes", "pkv_probe_read", "pkv_status_string"]
 
 
 class PkvError(RuntimeError):
@@ -87,6 +88,10 @@ def load() -> ctypes.CDLL:
         lib.pkv_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
         lib.pkv_decode_workspace_bytes.restype = ctypes.c_size_t
         lib.pkv_decode_attention.restype = ctypes.c_int
+        lib.pkv_decode_layers_workspace_bytes.argtypes = [i32, ctypes.POINTER(DecodeDesc)]
+        lib.pkv_decode_layers_workspace_bytes.restype = ctypes.c_size_t
+        lib.pkv_decode_attention_layers.argtypes = [i32, ctypes.POINTER(DecodeDesc)] + [vp] * 8 + [ctypes.c_size_t, vp]
+        lib.pkv_decode_attention_layers.restype = ctypes.c_int
         lib.pkv_status_string.argtypes = [ctypes.c_int]
         lib.pkv_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -324,6 +329,58 @@ def decode_attention(q: torch.Tensor, K_cache: torch.Tensor, V_cache: torch.Tens
     if rc != OK:
         raise PkvError(rc, "pkv_decode_attention")
     return out, lse
+
+
+class DecodeLayersCall:
+    """pkv_decode_attention_layers over the caches of L layers, marshalled once and launched any number of times.
+    qs[l] bf16 [B,Hq,d]; compact caches: K_caches[l], V_caches[l] bf16 [B,Hkv,k_cap_l,d] (any row strides); paged:
+    pools [num_pages_l,Hkv,page_size,d] with block_tables[l] int32 [B,max_pages_l] and k_caps[l]; counts[l] int32 [B].
+    outputs: list of (out fp32 [B,Hq,d], lse fp32 [B,Hq] or None)."""
+
+    def __init__(self, qs, K_caches, V_caches, counts, block_tables=None, k_caps=None, want_lse=False):
+        L = len(qs)
+        B, Hq, d = qs[0].shape
+        dev = qs[0].device
+        descs = (DecodeDesc * L)()
+        for l in range(L):
+            q, K, V = qs[l], K_caches[l], V_caches[l]
+            assert q.dtype == torch.bfloat16 and q.is_contiguous() and counts[l].dtype == torch.int32
+            assert K.dtype == torch.bfloat16 and V.dtype == torch.bfloat16
+            if block_tables is None:
+                assert K.stride() == V.stride() and K.stride(3) == 1
+                descs[l] = DecodeDesc(B, Hq, K.shape[1], d, K.shape[2], 0, 0, 0, 0, 0, K.stride(0), K.stride(1), K.stride(2))
+            else:
+                tb = block_tables[l]
+                assert K.is_contiguous() and V.is_contiguous() and tb.is_contiguous() and tb.dtype == torch.int32
+                descs[l] = DecodeDesc(B, Hq, K.shape[1], d, k_caps[l], K.shape[2], K.shape[0], tb.shape[1], 0, 0, 0, 0, 0)
+        self.L, self.descs, self.dev = L, descs, dev
+        self.keep = (qs, K_caches, V_caches, counts, block_tables)
+        self.outputs = [(torch.empty(B, Hq, d, dtype=torch.float32, device=dev),
+                         torch.empty(B, Hq, dtype=torch.float32, device=dev) if want_lse else None) for _ in range(L)]
+        arr = ctypes.c_void_p * L
+        self.a_q = arr(*[t.data_ptr() for t in qs])
+        self.a_K = arr(*[t.data_ptr() for t in K_caches])
+        self.a_V = arr(*[t.data_ptr() for t in V_caches])
+        self.a_tb = None if block_tables is None else arr(*[t.data_ptr() for t in block_tables])
+        self.a_cnt = arr(*[t.data_ptr() for t in counts])
+        self.a_out = arr(*[o[0].data_ptr() for o in self.outputs])
+        self.a_lse = arr(*[o[1].data_ptr() for o in self.outputs]) if want_lse else None
+        need = load().pkv_decode_layers_workspace_bytes(L, descs)
+        self.ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev) if need > 0 else None
+        self.ws_bytes = need
+
+    def run(self):
+        rc = load().pkv_decode_attention_layers(self.L, self.descs, self.a_q, self.a_K, self.a_V, self.a_tb, self.a_cnt,
+                                                self.a_out, self.a_lse, _p(self.ws), self.ws_bytes,
+                                                _stream_ptr(self.dev))
+        if rc != OK:
+            raise PkvError(rc, "pkv_decode_attention_layers")
+        return self.outputs
+
+
+def decode_attention_layers(qs, K_caches, V_caches, counts, block_tables=None, k_caps=None, want_lse=False):
+    """pkv_decode_attention_layers: one call for the caches of all layers.  Returns [(out, lse or None)] per layer."""
+    return DecodeLayersCall(qs, K_caches, V_caches, counts, block_tables, k_caps, want_lse).run()
 
 
 def compress_layers(Q_win, K, V, k_ls, pool, pool_w, seq_lens=None, want_scores=False):

@@ -524,6 +524,105 @@ int pkv_decode_attention(const pkv_decode_desc* desc, const void* q, const void*
   return launch_decode_attention(da, static_cast<hipStream_t>(stream)) == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
 
+// How the layers of a decoding step are cut into key ranges (from the descriptors alone).
+namespace {
+struct DecodeLayersPlan {
+  int chunk_target;
+  int64_t records;  // partial-result records of the layers with more than one range
+  bool ok;
+};
+DecodeLayersPlan decode_layers_plan(int32_t L, const pkv_decode_desc* descs) {
+  DecodeLayersPlan p = {0, 0, false};
+  if (L < 1 || L > kMaxLayers || !descs) return p;
+  int64_t rows = 0;
+  for (int32_t l = 0; l < L; ++l) {
+    if (check_decode_desc(&descs[l]) != PKV_OK) return p;
+    const pkv_decode_desc &d = descs[l], &d0 = descs[0];
+    if (d.B != d0.B || d.Hq != d0.Hq || d.Hkv != d0.Hkv || d.d != d0.d || d.page_size != d0.page_size) return p;
+    rows += (int64_t)d.B * d.Hkv * d.k_cap;
+  }
+  p.chunk_target = decode_layers_chunk(rows);
+  for (int32_t l = 0; l < L; ++l) {
+    int chunk;
+    const int S = decode_layers_splits(descs[l].k_cap, p.chunk_target, &chunk);
+    if (S > 1) p.records += (int64_t)descs[l].B * descs[l].Hkv * S;
+  }
+  p.ok = true;
+  return p;
+}
+}  // namespace
+
+size_t pkv_decode_layers_workspace_bytes(int32_t L, const pkv_decode_desc* descs) {
+  const DecodeLayersPlan p = decode_layers_plan(L, descs);
+  if (!p.ok) return 0;
+  return (size_t)p.records * (8 * (size_t)descs[0].d + 16) * sizeof(float);
+}
+
+int pkv_decode_attention_layers(int32_t L, const pkv_decode_desc* descs, const void* const* q,
+                                const void* const* K_cache, const void* const* V_cache,
+                                const int32_t* const* block_tables, const int32_t* const* count, float* const* out,
+                                float* const* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (L < 1 || L > kMaxLayers || !descs || !q || !K_cache || !V_cache || !count || !out) return PKV_ERR_INVALID_ARG;
+  for (int32_t l = 0; l < L; ++l) {
+    const int drc = check_decode_desc(&descs[l]);
+    if (drc != PKV_OK) return drc;
+  }
+  const DecodeLayersPlan plan = decode_layers_plan(L, descs);
+  if (!plan.ok) return PKV_ERR_INVALID_ARG;  // the layers differ in B, heads, d or page size
+  const pkv_decode_desc& d0 = descs[0];
+  if (d0.page_size > 0 && !block_tables) return PKV_ERR_INVALID_ARG;
+  for (int32_t l = 0; l < L; ++l) {
+    if (!q[l] || !K_cache[l] || !V_cache[l] || !count[l] || !out[l]) return PKV_ERR_INVALID_ARG;
+    if (!aligned16(q[l]) || !aligned16(K_cache[l]) || !aligned16(V_cache[l]) || ((uintptr_t)count[l] & 3) ||
+        ((uintptr_t)out[l] & 3) || (lse_out && ((uintptr_t)lse_out[l] & 3)))
+      return PKV_ERR_INVALID_ARG;
+    if (d0.page_size > 0 && (!block_tables[l] || ((uintptr_t)block_tables[l] & 3))) return PKV_ERR_INVALID_ARG;
+  }
+  const size_t need = (size_t)plan.records * (8 * (size_t)d0.d + 16) * sizeof(float);
+  if (need > 0 && (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)) return PKV_ERR_WORKSPACE;
+  float* part_o = static_cast<float*>(workspace);
+  float* part_mz = part_o ? part_o + (size_t)plan.records * 8 * d0.d : nullptr;
+  int64_t part0 = 0;
+  for (int32_t l0 = 0; l0 < L; l0 += kDecodeMaxLayers) {
+    const int32_t nl = L - l0 < kDecodeMaxLayers ? L - l0 : kDecodeMaxLayers;
+    DecodeBatchArgs a;
+    memset(&a, 0, sizeof(a));
+    a.part_o = part_o;
+    a.part_mz = part_mz;
+    a.L = nl; a.B = d0.B; a.Hq = d0.Hq; a.Hkv = d0.Hkv; a.G = d0.Hq / d0.Hkv; a.d = d0.d; a.page_size = d0.page_size;
+    a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)d0.d));
+    int64_t wg = 0;
+    int max_chunk = 0;
+    bool any_split = false;
+    for (int32_t i = 0; i < nl; ++i) {
+      const pkv_decode_desc& d = descs[l0 + i];
+      DecodeLayer& ly = a.layer[i];
+      ly.q = static_cast<const uint16_t*>(q[l0 + i]);
+      ly.K = static_cast<const uint16_t*>(K_cache[l0 + i]);
+      ly.V = static_cast<const uint16_t*>(V_cache[l0 + i]);
+      ly.table = d0.page_size > 0 ? block_tables[l0 + i] : nullptr;
+      ly.count = count[l0 + i];
+      ly.out = out[l0 + i];
+      ly.lse = lse_out ? lse_out[l0 + i] : nullptr;
+      ly.c_sb = d.c_sb; ly.c_sh = d.c_sh; ly.c_st = d.c_st;
+      ly.k_cap = d.k_cap; ly.num_pages = d.num_pages; ly.max_pages = d.max_pages;
+      ly.S = decode_layers_splits(d.k_cap, plan.chunk_target, &ly.chunk);
+      ly.wg0 = (int32_t)wg;
+      ly.part0 = (int32_t)part0;
+      wg += (int64_t)d.B * d.Hkv * ly.S;
+      if (ly.S > 1) {
+        part0 += (int64_t)d.B * d.Hkv * ly.S;
+        any_split = true;
+      }
+      if (ly.chunk > max_chunk) max_chunk = ly.chunk;
+    }
+    if (wg > 0x7FFFFFFF || part0 > 0x7FFFFFFF) return PKV_ERR_UNSUPPORTED;
+    if (launch_decode_attention_layers(a, (int)wg, max_chunk, any_split, static_cast<hipStream_t>(stream)) != hipSuccess)
+      return PKV_ERR_HIP;
+  }
+  return PKV_OK;
+}
+
 int pkv_budgets_schedule(int32_t L, int32_t avg_budget, int32_t beta, int32_t alpha, int32_t schedule,
                          int32_t* k_out) {
   if (schedule == PKV_SCHEDULE_LINEAR) return pkv_budgets(L, avg_budget, beta, alpha, k_out);

@@ -48,14 +48,13 @@ __device__ __forceinline__ const uint16_t* cache_row(const DecodeArgs& a, const 
   return base + (size_t)b * a.c_sb + (size_t)g * a.c_sh + (size_t)j * a.c_st;
 }
 
+// Key range sp of (sequence b, KV head g) of one layer's cache.
 // FINAL: S == 1, the result is written here; else partial results go to the workspace.
 template <int D, bool FINAL>
-__global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeArgs a) {
+__device__ __forceinline__ void decode_range(const DecodeArgs& a, int sp, int g, int b, float* dsm) {
   constexpr int KS = D / 16, SEG = D / 8, PITCH = SEG + 1;
-  extern __shared__ float dsm[];
-  // [8][chunk] logits / weights | [32 * PITCH] Q tile (16-byte slots) | [4][8][D] partial outputs | [8][2] (max, sum)
-  // | [kTabEntries] block-table entries of this key range
-  const int sp = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  // dsm: [8][chunk] logits / weights | [32 * PITCH] Q tile (16-byte slots) | [4][8][D] partial outputs | [8][2]
+  // (max, sum) | [kTabEntries] block-table entries of this key range
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int cnt = a.count[b];
   cnt = cnt < 0 ? 0 : (cnt > a.k_cap ? a.k_cap : cnt);
@@ -254,10 +253,15 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeAr
   }
 }
 
+template <int D, bool FINAL>
+__global__ __launch_bounds__(kThreads) void decode_partial_kernel(const DecodeArgs a) {
+  extern __shared__ float dsm[];
+  decode_range<D, FINAL>(a, blockIdx.x, blockIdx.y, blockIdx.z, dsm);
+}
+
 // Merge of the S partial results of a (sequence, KV head): common reference exponent, sums, weighted values.
 template <int D>
-__global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a) {
-  const int g = blockIdx.x, b = blockIdx.y;
+__device__ __forceinline__ void decode_merge(const DecodeArgs& a, int g, int b) {
   const size_t unit = (size_t)b * a.Hkv + g;
   const float* part_o = a.part_o + unit * a.S * 8 * D;
   const float* part_mz = a.part_mz + unit * a.S * 16;
@@ -288,6 +292,51 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a) {
     if (a.lse && e == h * D)
       a.lse[(size_t)b * a.Hq + g * a.G + h] = z > 0.f ? (M + __builtin_amdgcn_logf(z)) * 0.69314718055994530942f : -INFINITY;
   }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void decode_merge_kernel(const DecodeArgs a) {
+  decode_merge<D>(a, blockIdx.x, blockIdx.y);
+}
+
+// ---- all layers of a decoding step in one launch ----
+// The layers' caches are small at batch 1 (a few hundred rows each under a pyramidal budget), and a launch per layer
+// costs more than the rows it reads; here workgroup w of the grid finds its layer from the table's running workgroup
+// counts and works on one key range of one (sequence, KV head) of it, exactly as above.
+__device__ __forceinline__ DecodeArgs layer_args(const DecodeBatchArgs& a, int l) {
+  const DecodeLayer& ly = a.layer[l];
+  DecodeArgs d;
+  d.q = ly.q; d.K = ly.K; d.V = ly.V; d.table = ly.table; d.count = ly.count; d.out = ly.out; d.lse = ly.lse;
+  d.part_o = a.part_o + (size_t)ly.part0 * 8 * a.d;
+  d.part_mz = a.part_mz + (size_t)ly.part0 * 16;
+  d.B = a.B; d.Hq = a.Hq; d.Hkv = a.Hkv; d.G = a.G; d.d = a.d; d.k_cap = ly.k_cap;
+  d.page_size = a.page_size; d.num_pages = ly.num_pages; d.max_pages = ly.max_pages;
+  d.S = ly.S; d.chunk = ly.chunk;
+  d.c_sb = ly.c_sb; d.c_sh = ly.c_sh; d.c_st = ly.c_st;
+  d.scale_log2 = a.scale_log2;
+  return d;
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void decode_partial_layers_kernel(const DecodeBatchArgs a) {
+  extern __shared__ float dsm[];
+  const int w = blockIdx.x;
+  int l = 0;
+  while (l + 1 < a.L && w >= a.layer[l + 1].wg0) ++l;  // (wave-uniform: scalar loads from the argument table)
+  const DecodeArgs d = layer_args(a, l);
+  const int rel = w - a.layer[l].wg0;          // [b][g][sp]
+  const int sp = rel % d.S, bg = rel / d.S;
+  const int g = bg % a.Hkv, b = bg / a.Hkv;
+  if (d.S == 1) decode_range<D, true>(d, sp, g, b, dsm);
+  else decode_range<D, false>(d, sp, g, b, dsm);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void decode_merge_layers_kernel(const DecodeBatchArgs a) {
+  const int l = blockIdx.z;
+  if (a.layer[l].S == 1) return;  // that layer's ranges wrote the result themselves
+  const DecodeArgs d = layer_args(a, l);
+  decode_merge<D>(d, blockIdx.x, blockIdx.y);
 }
 
 size_t lds_bytes(int d, int chunk) {
@@ -322,6 +371,25 @@ hipError_t launch(const DecodeArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int D>
+hipError_t launch_layers(const DecodeBatchArgs& a, int total_wgs, int max_chunk, bool any_split, hipStream_t s) {
+  const size_t lds = lds_bytes(D, max_chunk);
+  static size_t granted_all[kMaxDevices];
+  const int dev = current_device_slot();
+  if (dev < 0) return hipErrorInvalidDevice;
+  if (lds > granted_all[dev]) {  // raise the dynamic LDS limit when a larger range comes along (no allocation)
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_layers_kernel<D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    granted_all[dev] = lds;
+  }
+  hipLaunchKernelGGL(decode_partial_layers_kernel<D>, dim3(total_wgs), dim3(kThreads), lds, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !any_split) return e;
+  hipLaunchKernelGGL(decode_merge_layers_kernel<D>, dim3(a.Hkv, a.B, a.L), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 // Key ranges per (sequence, KV head): enough workgroups to fill the chip, at least 128 keys each.
@@ -331,6 +399,27 @@ int decode_splits(int B, int Hkv, int k_cap) {
   const int by_len = k_cap / 128;
   if (S > by_len) S = by_len;
   return S < 1 ? 1 : S;
+}
+
+// All layers in one launch: keys per range so that the layers together give about 2048 workgroups, between 128 and
+// 1024 keys (multiple of 32); a layer's cache is cut into at most 16 ranges of that size.
+int decode_layers_chunk(int64_t rows_total) {
+  int64_t c = (rows_total + 2047) / 2048;
+  c = c < 128 ? 128 : (c > 1024 ? 1024 : c);
+  return (int)((c + 31) / 32 * 32);
+}
+int decode_layers_splits(int k_cap, int chunk_target, int* chunk) {
+  int S = (k_cap + chunk_target - 1) / chunk_target;
+  S = S < 1 ? 1 : (S > kMaxSplits ? kMaxSplits : S);
+  *chunk = ((k_cap + S - 1) / S + 31) / 32 * 32;
+  return S;
+}
+
+hipError_t launch_decode_attention_layers(const DecodeBatchArgs& a, int total_wgs, int max_chunk, bool any_split,
+                                          hipStream_t s) {
+  if (a.d == 128) return launch_layers<128>(a, total_wgs, max_chunk, any_split, s);
+  if (a.d == 64) return launch_layers<64>(a, total_wgs, max_chunk, any_split, s);
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_decode_attention(const DecodeArgs& a, hipStream_t s) {

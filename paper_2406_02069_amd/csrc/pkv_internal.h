@@ -176,6 +176,35 @@ struct DecodeArgs {
 int decode_splits(int B, int Hkv, int k_cap);
 hipError_t launch_decode_attention(const DecodeArgs& a, hipStream_t s);
 
+// The same over the caches of several layers in one launch (per-layer pointers and cache sizes; shape shared).
+struct DecodeLayer {
+  const uint16_t* q;
+  const uint16_t* K;
+  const uint16_t* V;
+  const int32_t* table;
+  const int32_t* count;
+  float* out;
+  float* lse;
+  int64_t c_sb, c_sh, c_st;
+  int32_t k_cap, num_pages, max_pages;
+  int32_t S, chunk;  // key ranges of this layer; keys per range
+  int32_t wg0;       // first workgroup of this layer in the launch: layers follow one another, [b][g][range] inside
+  int32_t part0;     // first partial-result record of this layer in the workspace ([b][g][range] inside)
+  int32_t pad;
+};
+constexpr int kDecodeMaxLayers = 32;  // per launch (kernel-argument table)
+struct DecodeBatchArgs {
+  DecodeLayer layer[kDecodeMaxLayers];
+  float* part_o;   // [records][8][d]
+  float* part_mz;  // [records][8][2]
+  int32_t L, B, Hq, Hkv, G, d, page_size;
+  float scale_log2;
+};
+int decode_layers_chunk(int64_t rows_total);
+int decode_layers_splits(int k_cap, int chunk_target, int* chunk);
+hipError_t launch_decode_attention_layers(const DecodeBatchArgs& a, int total_wgs, int max_chunk, bool any_split,
+                                          hipStream_t s);
+
 // Index of the current device for per-device launch state (dynamic LDS limits are set per device), or -1.
 constexpr int kMaxDevices = 64;
 inline int current_device_slot() {

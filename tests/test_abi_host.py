@@ -265,3 +265,39 @@ def test_decode_attention_rejects_bad_arguments():
     assert lib.pkv_decode_workspace_bytes(ctypes.byref(desc(B=64))) == 0
     assert lib.pkv_decode_attention(ctypes.byref(big), 0x1000, 0x2000, 0x3000, None, 0x4000, 0x5000, None, 0x10000,
                                     need - 1, None) == binding.ERR_WORKSPACE
+
+
+def test_decode_attention_layers_rejects_bad_arguments():
+    lib = binding.load()
+    I, U = binding.ERR_INVALID_ARG, binding.ERR_UNSUPPORTED
+
+    def desc(**kw):
+        base = dict(B=1, Hq=32, Hkv=8, d=128, k_cap=256, page_size=0, num_pages=0, max_pages=0, reserved=0, reserved2=0,
+                    c_sb=8 * 256 * 128, c_sh=256 * 128, c_st=128)
+        base.update(kw)
+        return binding.DecodeDesc(**base)
+
+    arr = lambda *v: (ctypes.c_void_p * len(v))(*v)
+    good = arr(0x1000, 0x2000)
+
+    def call(descs, q=good, K=good, V=good, tb=None, cnt=good, out=good, lse=None, ws=0x10000, ws_bytes=1 << 30):
+        return lib.pkv_decode_attention_layers(len(descs), descs, q, K, V, tb, cnt, out, lse, ws, ws_bytes, None)
+
+    two = (binding.DecodeDesc * 2)(desc(), desc(k_cap=4096, c_sb=8 * 4096 * 128, c_sh=4096 * 128))
+    assert call(two, q=None) == I and call(two, out=None) == I and call(two, cnt=None) == I
+    assert call(two, K=arr(0x1000, None)) == I and call(two, V=arr(0x1000, 0x2004)) == I
+    assert lib.pkv_decode_attention_layers(0, two, good, good, good, None, good, good, None, 0x10000, 1 << 30, None) == I
+    assert call((binding.DecodeDesc * 2)(desc(), desc(Hq=16))) == I            # the layers differ in their heads
+    assert call((binding.DecodeDesc * 2)(desc(), desc(B=2))) == I
+    assert call((binding.DecodeDesc * 2)(desc(), desc(d=96))) == U
+    assert call((binding.DecodeDesc * 2)(desc(), desc(k_cap=5000))) == U
+    paged = (binding.DecodeDesc * 2)(desc(page_size=16, num_pages=64, max_pages=16),
+                                     desc(page_size=16, num_pages=64, max_pages=16))
+    assert call(paged) == I and call(paged, tb=arr(0x6000, None)) == I          # paged without (all) tables
+    # 8 heads x (256 + 4096) rows = 34 816 rows: 128-key ranges, so 2 and 16 (the most) ranges per head
+    need = lib.pkv_decode_layers_workspace_bytes(2, two)
+    assert need == 8 * (2 + 16) * (8 * 128 + 16) * 4
+    assert call(two, ws_bytes=need - 1) == binding.ERR_WORKSPACE and call(two, ws=None) == binding.ERR_WORKSPACE
+    one = (binding.DecodeDesc * 1)(desc(k_cap=100, c_sb=8 * 100 * 128, c_sh=100 * 128))
+    assert lib.pkv_decode_layers_workspace_bytes(1, one) == 0                   # a single range per head: no partials
+    assert lib.pkv_decode_layers_workspace_bytes(2, (binding.DecodeDesc * 2)(desc(), desc(Hq=16))) == 0

@@ -124,3 +124,93 @@ def test_compact_cache_behind_compress_layer_and_bad_pages_count_as_absent():
     Kc[1, :, : k_l - P] = Ko[1][:, keep]
     Vc[1, :, : k_l - P] = Vo[1][:, keep]
     _cmp(out2, None, Kc, Vc, qd, np.array([k_l, k_l - P], dtype=np.int32))
+
+
+# ---- all layers of a decoding step in one call (pkv_decode_attention_layers) ----
+
+def _layers_case(B, Hq, Hkv, d, k_caps, seed, ragged=True):
+    qs, Ks, Vs, counts = [], [], [], []
+    rs = np.random.RandomState(seed)
+    for l, k_cap in enumerate(k_caps):
+        q, K, V = _rand(B, Hq, Hkv, d, k_cap, seed=seed * 1000 + l, scale=2.0)
+        c = rs.randint(0, k_cap + 1, size=B).astype(np.int32) if ragged else np.full(B, k_cap, dtype=np.int32)
+        c[0] = k_cap
+        qs.append(q); Ks.append(K); Vs.append(V); counts.append(c)
+    return qs, Ks, Vs, counts
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,d,k_caps", [
+    (1, 32, 8, 128, [242, 166, 90, 14]),                      # a small pyramid at batch 1: one range per head
+    (1, 32, 8, 128, [3963, 2730, 1500, 700, 133, 1]),         # a steep pyramid: 16 ... 1 ranges per head
+    (3, 8, 2, 64, [4096, 33, 777, 128, 129]),
+    (8, 32, 8, 128, [2048, 300]),
+    (2, 8, 8, 64, list(range(1, 70, 2))),                     # 35 layers: more than one launch's table holds
+])
+def test_layers_call_compact_caches(B, Hq, Hkv, d, k_caps):
+    qs, Ks, Vs, counts = _layers_case(B, Hq, Hkv, d, k_caps, seed=B + Hq + len(k_caps))
+    print("decode layers", B, Hq, Hkv, d, k_caps[:6], flush=True)
+    outs = binding.decode_attention_layers(qs, Ks, Vs, [torch.from_numpy(c).to(DEV) for c in counts], want_lse=True)
+    torch.cuda.synchronize()
+    for l, (out, lse) in enumerate(outs):
+        _cmp(out, lse, Ks[l], Vs[l], qs[l], counts[l])
+        # and the per-layer entry gives the same up to the order of the fp32 additions
+        one, _ = binding.decode_attention(qs[l], Ks[l], Vs[l], torch.from_numpy(counts[l]).to(DEV))
+        torch.cuda.synchronize()
+        scale = float(Vs[l].float().abs().max())
+        assert float((one - out).abs().max()) <= 4e-5 * scale
+
+
+def test_layers_call_without_lse_and_strided_caches():
+    B, Hq, Hkv, d = 2, 8, 2, 128
+    k_caps = [100, 1000]
+    qs, Ks, Vs, counts = _layers_case(B, Hq, Hkv, d, k_caps, seed=77)
+    bigK = [torch.zeros(B, Hkv, k + 5, d + 64, dtype=torch.bfloat16, device=DEV) for k in k_caps]
+    bigV = [torch.zeros_like(x) for x in bigK]
+    for l, k in enumerate(k_caps):
+        bigK[l][:, :, :k, :d] = Ks[l]
+        bigV[l][:, :, :k, :d] = Vs[l]
+    outs = binding.decode_attention_layers(qs, [x[:, :, :k, :d] for x, k in zip(bigK, k_caps)],
+                                           [x[:, :, :k, :d] for x, k in zip(bigV, k_caps)],
+                                           [torch.from_numpy(c).to(DEV) for c in counts])
+    torch.cuda.synchronize()
+    for l, (out, lse) in enumerate(outs):
+        assert lse is None
+        _cmp(out, None, Ks[l], Vs[l], qs[l], counts[l])
+
+
+@pytest.mark.parametrize("page_size", [16, 17])
+def test_layers_call_behind_the_paged_compression(page_size):
+    # end to end over three layers with a pyramid of budgets: compress into per-layer page pools, attend over all
+    # layers' pools in one call; reference: oracle compression + oracle attention per layer
+    alpha, k_ls = 8, [600, 150, 40]
+    B, Hq, Hkv, d, N = 2, 8, 2, 128, 900
+    g = torch.Generator(device=DEV).manual_seed(100 + page_size)
+    L = len(k_ls)
+    Qs = [torch.randn(B, Hq, alpha, d, generator=g, device=DEV).to(torch.bfloat16) for _ in range(L)]
+    Ks = [torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16) for _ in range(L)]
+    Vs = [torch.randn(B, Hkv, N, d, generator=g, device=DEV).to(torch.bfloat16) for _ in range(L)]
+    lens = np.array([900, 333], dtype=np.int32)
+    rs = np.random.RandomState(page_size)
+    tables, Kp, Vp = [], [], []
+    max_pages = (max(k_ls) + page_size - 1) // page_size     # the compression call takes one pool shape for all layers
+    num_pages = B * max_pages + 3
+    for k_l in k_ls:
+        tables.append(torch.from_numpy(rs.permutation(num_pages)[: B * max_pages].astype(np.int32)
+                                       .reshape(B, max_pages)).to(DEV))
+        Kp.append(torch.full((num_pages, Hkv, page_size, d), float("nan"), dtype=torch.bfloat16, device=DEV))
+        Vp.append(Kp[-1].clone())
+    outs = binding.compress_layers_paged(Qs, Ks, Vs, k_ls, synth.POOL_MAX, 7, Kp, Vp, tables, page_size,
+                                         seq_lens=torch.from_numpy(lens).to(DEV))
+    qd = [torch.randn(B, Hq, d, generator=g, device=DEV).to(torch.bfloat16) for _ in range(L)]
+    res = binding.decode_attention_layers(qd, Kp, Vp, [o[3] for o in outs], block_tables=tables, k_caps=k_ls,
+                                          want_lse=True)
+    torch.cuda.synchronize()
+    for l in range(L):
+        out, lse = res[l]
+        assert not torch.isnan(out).any()
+        ref = pkv_oracle.compress_layer(Qs[l], Ks[l], Vs[l], k_ls[l], alpha, synth.POOL_MAX, 7, seq_lens=lens,
+                                        want_pooled=False)
+        np.testing.assert_array_equal(outs[l][2].cpu().numpy(), ref["idx"])
+        Kc = torch.from_numpy(ref["K_out"].view(np.int16)).view(torch.bfloat16)
+        Vc = torch.from_numpy(ref["V_out"].view(np.int16)).view(torch.bfloat16)
+        _cmp(out, lse, Kc, Vc, qd[l], ref["count"])

@@ -401,11 +401,13 @@ int decode_splits(int B, int Hkv, int k_cap) {
   return S < 1 ? 1 : S;
 }
 
-// All layers in one launch: keys per range so that the layers together give about 2048 workgroups, between 128 and
-// 1024 keys (multiple of 32); a layer's cache is cut into at most 16 ranges of that size.
+// All layers in one launch: keys per range so that the layers together give about 512 workgroups, between 256 and
+// 1024 keys (multiple of 32); a layer's cache is cut into at most 16 ranges of that size.  (Measured on caches of
+// 0.02 to 2 GB per step: 256 to 1024 workgroups are equally fast, more are slower (the merge grows); caches that fit
+// one range per head skip the merge launch, which is a third of the time of a small step.)
 int decode_layers_chunk(int64_t rows_total) {
-  int64_t c = (rows_total + 2047) / 2048;
-  c = c < 128 ? 128 : (c > 1024 ? 1024 : c);
+  int64_t c = (rows_total + 511) / 512;
+  c = c < 256 ? 256 : (c > 1024 ? 1024 : c);
   return (int)((c + 31) / 32 * 32);
 }
 int decode_layers_splits(int k_cap, int chunk_target, int* chunk) {

@@ -294,9 +294,10 @@ def test_decode_attention_layers_rejects_bad_arguments():
     paged = (binding.DecodeDesc * 2)(desc(page_size=16, num_pages=64, max_pages=16),
                                      desc(page_size=16, num_pages=64, max_pages=16))
     assert call(paged) == I and call(paged, tb=arr(0x6000, None)) == I          # paged without (all) tables
-    # 8 heads x (256 + 4096) rows = 34 816 rows: 128-key ranges, so 2 and 16 (the most) ranges per head
+    # 8 heads x (256 + 4096) rows = 34 816 rows: 256-key ranges (the smallest), so 1 and 16 ranges per head; only
+    # the layer with more than one range needs partial results
     need = lib.pkv_decode_layers_workspace_bytes(2, two)
-    assert need == 8 * (2 + 16) * (8 * 128 + 16) * 4
+    assert need == 8 * 16 * (8 * 128 + 16) * 4
     assert call(two, ws_bytes=need - 1) == binding.ERR_WORKSPACE and call(two, ws=None) == binding.ERR_WORKSPACE
     one = (binding.DecodeDesc * 1)(desc(k_cap=100, c_sb=8 * 100 * 128, c_sh=100 * 128))
     assert lib.pkv_decode_layers_workspace_bytes(1, one) == 0                   # a single range per head: no partials

@@ -112,7 +112,7 @@ def verify_against_oracle(w, ks, Qs, Ks, Vs, lens, lens_dev, timed_outputs, veri
     return tot
 
 
-def measure(w, avg, steps, warmup, dev, lse=False, page_size=0, host_layers=(), want_read_probe=True):
+def measure(w, avg, steps, warmup, dev, lse=False, page_size=0, host_layers=(), want_read_probe=True, graph=False):
     """Generates the workload on the device, runs the legs described at the top, returns (result dict, context)."""
     import numpy as np
     import torch
@@ -164,14 +164,22 @@ def measure(w, avg, steps, warmup, dev, lse=False, page_size=0, host_layers=(), 
     dominant = max(sum_ms, key=sum_ms.get)
 
     # (2) warm-up, (3) the timed steps
+    step = call.run
+    if graph:   # variant: the step recorded once into a HIP graph (on a side stream) and replayed
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                call.run()
+        step = g.replay
     for _ in range(warmup):
-        call.run()
+        step()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]   # torch's current stream = launch stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev[0].record()
     for i in range(steps):
-        call.run()
+        step()
         ev[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -266,6 +274,9 @@ def main():
     ap.add_argument("--lse", action="store_true",
                     help="variant: one-sweep scoring with the window queries' softmax denominators supplied "
                          "(computed beforehand, outside the timed region); not the headline configuration")
+    ap.add_argument("--graph", action="store_true",
+                    help="variant: the timed steps replay a HIP graph of the step instead of launching its kernels "
+                         "one by one; not the headline configuration")
     ap.add_argument("--page-size", type=int, default=0,
                     help="variant: kept rows written into per-layer page pools of this page size through random "
                          "block tables (pkv_compress_layers_paged); not the headline configuration")
@@ -292,7 +303,7 @@ def main():
     else:
         args.seq_len = None
     avg = args.avg_budget or w.avg_budgets[0]
-    variant = args.lse or args.page_size > 0 or args.seq_len is not None
+    variant = args.lse or args.page_size > 0 or args.seq_len is not None or args.graph
     if variant:
         args.no_cpu_baseline = True
         args.no_all_configs = True
@@ -301,7 +312,7 @@ def main():
         args.no_all_configs = True
     host_layers = () if args.no_cpu_baseline else tuple(range(w.L))[: 32]
     res, ctx = measure(w, avg, args.steps, args.warmup, dev, lse=args.lse, page_size=args.page_size,
-                       host_layers=host_layers)
+                       host_layers=host_layers, graph=args.graph)
     call, ks, lens, lens_dev, paged = ctx["call"], ctx["ks"], ctx["lens"], ctx["lens_dev"], ctx["paged"]
     Qs, Ks, Vs, lses = ctx["Qs"], ctx["Ks"], ctx["Vs"], ctx["lses"]
 
@@ -309,7 +320,8 @@ def main():
         "metric": METRIC +
                   (" [variant: softmax denominators supplied, one sweep]" if args.lse else "") +
                   (f" [variant: paged output, page size {args.page_size}]" if args.page_size > 0 else "") +
-                  (f" [variant: context length {args.seq_len}]" if args.seq_len is not None else ""),
+                  (f" [variant: context length {args.seq_len}]" if args.seq_len is not None else "") +
+                  (" [variant: step replayed from a HIP graph]" if args.graph else ""),
         "value": res["value"],
         "unit": "tokens/s",
         "n_gpus": 1,

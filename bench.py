@@ -421,6 +421,15 @@ def main():
         ctx.clear()
         gc.collect()
         torch.cuda.empty_cache()
+        # The same workload through pkv_compress_layers_lse (denominators supplied by the caller's attention kernel;
+        # here by tests/prefill_stub.py, outside any timing): a variant, reported beside the headline, never as it.
+        r, c = measure(w, avg, 20, 10, dev, lse=True, want_read_probe=False)
+        out["variant_supplied_denominators"] = {"ms_per_step": r["ms_per_step"], "value": r["value"], "unit": "tokens/s",
+                                                "kernel_ms_per_step": r["kernel_ms_per_step"], "roofline": r["roofline"]}
+        c.clear()
+        del r, c
+        gc.collect()
+        torch.cuda.empty_cache()
         out["all_configs"] = []
         for ci in (0, 1, 3, 4, 5):
             wc = (synth.WORKLOADS + synth.EXTRA_WORKLOADS)[ci]

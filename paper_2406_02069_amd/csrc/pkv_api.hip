@@ -208,7 +208,10 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
       ra.L = nl; ra.B = d.B; ra.Hq = d.Hq; ra.Hkv = d.Hkv; ra.G = plan.G; ra.alpha = d.alpha; ra.N = d.N;
       ra.R = plan.R; ra.Rpad = plan.res_Rpad; ra.nrb = plan.res_nrb; ra.TPU = plan.TPU;
       ra.ngroups = plan.ngroups; ra.UPG = plan.UPG;
-      ra.stagger = lse_mode ? 0 : kResidentStagger;
+      // staggered starts pay when a group has many units to drift apart over (32k workload, 32 units per group:
+      // 2.5 % faster than a common start); on a short launch the delay itself weighs more than the drift gains
+      // (8k workload, 8 units per group: 5 % slower; tiny workload: 25 %)
+      ra.stagger = (lse_mode || ra.U < 16 * plan.ngroups * plan.UPG) ? 0 : kResidentStagger;
       ra.wait_ticks = (d.flags & PKV_FLAG_NO_WAIT) ? 0 : kResidentWaitTicks;
       // the tagged exchange (every part of a group takes part in every unit, also one that lies beyond the end of a
       // shorter sequence) is worth it when a unit has enough parts to spread the rows over

@@ -21,7 +21,7 @@ typedef enum {
      register-resident kernel would serve the shape: lets tests run both */
   PKV_FLAG_STREAM_SCORING = 1,
   /* exchange the softmax statistics through the arrival counter where the
-     tagged exchange would be used (units of 16 parts or more) */
+     tagged exchange would be used (units of 4 parts or more) */
   PKV_FLAG_COUNTER_EXCHANGE = 2,
   /* every bounded wait between workgroups gives up at once: forces, from the
      host, the outcome a caller sees when the resident kernel's workgroups

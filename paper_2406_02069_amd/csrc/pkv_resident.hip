@@ -24,7 +24,7 @@
 //   3. arrives at the unit's counter.  The last part to arrive folds all parts into the per-row
 //      normaliser c_r = max + log2(sum) and publishes it, tagged with the unit number; the others poll
 //      the tagged words.  (Agent-scope relaxed atomics: written through, never served from a stale line.)
-//      When a unit has 16 parts or more, every part takes part in every unit of its group (one beyond the end
+//      When a unit has 4 parts or more, every part takes part in every unit of its group (one beyond the end
 //      of a shorter sequence contributes neutral statistics) and there is no counter: the statistics
 //      words carry a phase bit, and part p folds the rows p, p + nparts, ... as soon as their words show
 //      it.

@@ -89,7 +89,7 @@ def test_config3_mistral_ragged_batch():
 
 
 def test_config3_mistral_ragged_batch_with_the_arrival_counter(monkeypatch):
-    # the exchange of softmax statistics through the arrival counter (the default for units of fewer than 16 parts)
+    # the exchange of softmax statistics through the arrival counter (the default for units of fewer than 4 parts)
     # at a size where the tagged exchange would be used
     monkeypatch.setattr(binding, "DESC_FLAGS", binding.FLAG_COUNTER_EXCHANGE)
     _full(3, 1)

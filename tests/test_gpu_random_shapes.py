@@ -50,7 +50,7 @@ def test_random_shape(seed, path, monkeypatch):
 
 @pytest.mark.parametrize("seed", range(8))
 def test_random_ragged_batch_with_many_parts(seed):
-    """Units of 16 parts or more in a ragged batch: the tagged exchange of the softmax statistics with parts that lie
+    """Units of many parts (16 or more) in a ragged batch: the tagged exchange of the softmax statistics with parts that lie
     beyond the end of a shorter sequence (they take part with neutral statistics), several layers so that every
     group of workgroups works through more than one unit."""
     rs = np.random.RandomState(300 + seed)

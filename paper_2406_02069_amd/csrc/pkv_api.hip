@@ -149,6 +149,11 @@ static bool device_fits_resident() {
 // Start offset between consecutive workgroup groups of the two-sweep resident kernel, in 10 ns ticks.
 constexpr int kResidentStagger = 250;
 
+// Largest per-layer budget up to which the kept rows are copied by the selection kernel itself.
+constexpr int kFuseGatherRows = 512;
+// ... or number of units (layers x sequences x KV heads) of a launch from which on it does so whatever the budget.
+constexpr int kFuseGatherUnits = 1024;
+
 // Share (of 32) of a group pair's units that the group of second workgroups takes.  Measured on the 32k workload:
 // with the arrival counter 15 beats equal shares (16) by 1.7 %; with the tagged exchange the second workgroups wait
 // less and equal shares are ahead by 0.7 %.
@@ -301,10 +306,18 @@ static int run_layers(int32_t L, const pkv_layer_desc* descs, const Plan& plan, 
     if (paged) {
       ga.page_size = paged->page_size; ga.num_pages = paged->num_pages; ga.max_pages = paged->max_pages;
     }
-    if (launch_pool_select_batch(se, nl, stream) != hipSuccess) return PKV_ERR_HIP;
+    // Few kept rows per head: the selection workgroup of a unit copies them itself (a gather launch of its own costs
+    // more than the copy; 8k workload: select + gather 34 -> 26.5 us).  So it does when there are several units per
+    // compute unit anyway (ragged batch at average budget 2048: 0.976 -> 0.909 ms).  Many rows of few units (32k
+    // workload at average budget 2048: the fused copy would take 0.165 instead of 0.045 + 0.089 ms), or page pools
+    // (whose bad-page report must come after the counts are written): the gather kernel, spread over the chip.
+    const bool fuse_gather = !paged && (k_cap_max <= kFuseGatherRows || (int64_t)nl * plan.BH >= kFuseGatherUnits);
+    if (launch_pool_select_batch(se, ga, fuse_gather, nl, stream) != hipSuccess) return PKV_ERR_HIP;
     if (rec) rec->after(PKV_KERNEL_POOL_SELECT, stream);
-    if (launch_gather_batch(ga, stream) != hipSuccess) return PKV_ERR_HIP;
-    if (rec) rec->after(PKV_KERNEL_GATHER, stream);
+    if (!fuse_gather) {
+      if (launch_gather_batch(ga, stream) != hipSuccess) return PKV_ERR_HIP;
+      if (rec) rec->after(PKV_KERNEL_GATHER, stream);
+    }
   }
   return PKV_OK;
 }

@@ -24,30 +24,7 @@ __global__ __launch_bounds__(256) void gather_batch_kernel(const GatherBatchArgs
   const int t = blockIdx.x * 256 + threadIdx.x;
   const int j = t / LPR, seg = t - j * LPR;
   if (j >= ly.k_cap) return;
-  const int src = ly.idx[(size_t)bg * ly.k_cap + j];
-  if (a.page_size > 0) {
-    if ((uint32_t)src >= (uint32_t)a.N) return;  // unused slot: the pool keeps its content
-    const int q = j / a.page_size, slot = j - q * a.page_size;
-    const int pg = q < a.max_pages ? ly.table[(size_t)b * a.max_pages + q] : -1;
-    if ((uint32_t)pg >= (uint32_t)a.num_pages) {  // never written through a bad page number: reported instead
-      ly.count_out[b] = -2;
-      return;
-    }
-    const size_t off = (size_t)b * a.kv_sb + (size_t)g * a.kv_sh + (size_t)src * a.kv_st + seg * 8;
-    const size_t o = (((size_t)pg * a.Hkv + g) * a.page_size + slot) * D + seg * 8;
-    *reinterpret_cast<uint4*>(ly.K_out + o) = *reinterpret_cast<const uint4*>(ly.K + off);
-    *reinterpret_cast<uint4*>(ly.V_out + o) = *reinterpret_cast<const uint4*>(ly.V + off);
-    return;
-  }
-  uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
-  if ((uint32_t)src < (uint32_t)a.N) {  // -1 marks an unused slot; anything else out of range is not dereferenced either
-    const size_t off = (size_t)b * a.kv_sb + (size_t)g * a.kv_sh + (size_t)src * a.kv_st + seg * 8;
-    kv = *reinterpret_cast<const uint4*>(ly.K + off);
-    vv = *reinterpret_cast<const uint4*>(ly.V + off);
-  }
-  const size_t o = (size_t)b * ly.o_sb + (size_t)g * ly.o_sh + (size_t)j * ly.o_st + seg * 8;
-  *reinterpret_cast<uint4*>(ly.K_out + o) = kv;
-  *reinterpret_cast<uint4*>(ly.V_out + o) = vv;
+  gather_row_segment(a, ly, b, g, j, seg);
 }
 
 // Plain streaming read (bandwidth probe): every lane folds its 16-byte words into a checksum.

@@ -100,7 +100,7 @@ struct ResidentArgs {
 };
 
 // ---- pooling + selection and gather over many layers ----
-constexpr int kBatchMaxLayers = 40;  // per launch (kernel-argument table)
+constexpr int kBatchMaxLayers = 32;  // per launch (kernel-argument tables: selection + gather together < 4 KB)
 
 struct SelectLayer {
   float* pooled;       // [BH][N]: scores_out of the layer, else workspace
@@ -140,6 +140,37 @@ struct GatherBatchArgs {
   int32_t page_size, num_pages, max_pages;  // page_size 0: compact output through the o_* strides
   int64_t kv_sb, kv_sh, kv_st;
 };
+
+// 16 bytes (segment seg) of kept row j of (sequence b, KV head g): from the cache into the compact cache or the
+// layer's page pool.  An index outside [0, N) is never dereferenced: the compact slot is cleared, a pool slot is
+// left alone.  d / 8 neighbouring lanes move one row.
+__device__ __forceinline__ void gather_row_segment(const GatherBatchArgs& a, const GatherLayer& ly, int b, int g, int j,
+                                                   int seg) {
+  const int src = ly.idx[((size_t)b * a.Hkv + g) * ly.k_cap + j];
+  if (a.page_size > 0) {
+    if ((uint32_t)src >= (uint32_t)a.N) return;  // unused slot: the pool keeps its content
+    const int q = j / a.page_size, slot = j - q * a.page_size;
+    const int pg = q < a.max_pages ? ly.table[(size_t)b * a.max_pages + q] : -1;
+    if ((uint32_t)pg >= (uint32_t)a.num_pages) {  // never written through a bad page number: reported instead
+      ly.count_out[b] = -2;
+      return;
+    }
+    const size_t off = (size_t)b * a.kv_sb + (size_t)g * a.kv_sh + (size_t)src * a.kv_st + seg * 8;
+    const size_t o = (((size_t)pg * a.Hkv + g) * a.page_size + slot) * a.d + seg * 8;
+    *reinterpret_cast<uint4*>(ly.K_out + o) = *reinterpret_cast<const uint4*>(ly.K + off);
+    *reinterpret_cast<uint4*>(ly.V_out + o) = *reinterpret_cast<const uint4*>(ly.V + off);
+    return;
+  }
+  uint4 kv = make_uint4(0, 0, 0, 0), vv = kv;
+  if ((uint32_t)src < (uint32_t)a.N) {  // -1 marks an unused slot; anything else out of range is not dereferenced either
+    const size_t off = (size_t)b * a.kv_sb + (size_t)g * a.kv_sh + (size_t)src * a.kv_st + seg * 8;
+    kv = *reinterpret_cast<const uint4*>(ly.K + off);
+    vv = *reinterpret_cast<const uint4*>(ly.V + off);
+  }
+  const size_t o = (size_t)b * ly.o_sb + (size_t)g * ly.o_sh + (size_t)j * ly.o_st + seg * 8;
+  *reinterpret_cast<uint4*>(ly.K_out + o) = kv;
+  *reinterpret_cast<uint4*>(ly.V_out + o) = vv;
+}
 
 // ---- attention recall of the kept set, from the un-pooled scores a compress call left in its workspace ----
 struct RecallLayer {
@@ -215,7 +246,9 @@ inline int current_device_slot() {
 
 hipError_t launch_score_resident(const ResidentArgs& a, hipStream_t s);
 hipError_t launch_recall(const RecallArgs& a, int nlayers, hipStream_t s);
-hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipStream_t s);
+// fuse_gather: the selection workgroup of a unit also copies the unit's kept rows (compact output only)
+hipError_t launch_pool_select_batch(const SelectBatchArgs& a, const GatherBatchArgs& ga, bool fuse_gather, int nlayers,
+                                    hipStream_t s);
 hipError_t launch_gather_batch(const GatherBatchArgs& a, hipStream_t s);
 hipError_t launch_probe_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t s);
 

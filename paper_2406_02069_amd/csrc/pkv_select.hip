@@ -634,7 +634,10 @@ __device__ __forceinline__ void select_unit(const float* raw, int nrb, size_t rb
   for (int t = tid; t < alpha; t += NT) idx[kk + t] = npre + t;
 }
 
-__global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatchArgs a) {
+// fuse_gather: once the unit's kept positions are written, the same workgroup copies the unit's K and V rows
+// (a7): for the few hundred rows of a small budget a launch of its own costs more than the copy.
+__global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatchArgs a, const GatherBatchArgs ga,
+                                                               const int fuse_gather) {
   extern __shared__ uint32_t lkeys[];  // kLdsKeys entries
   __shared__ uint32_t hist[HIST];
   __shared__ uint32_t scan32[2 * NW];
@@ -657,8 +660,51 @@ __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatch
   // a scoring kernel that gave up a wait leaves meaningless scores: the caller learns it from the count
   if (g == 0 && tid == 0) ly.count_out[b] = (a.err && *a.err != 0) ? -1 : count;
   int32_t* idx = ly.idx_out + (size_t)bg * ly.k_cap;
+  auto gather_unit = [&]() {
+    if (!fuse_gather) return;
+    __syncthreads();  // the unit's kept positions are complete (all of them written by this workgroup)
+    const GatherLayer& gl = ga.layer[l];
+    const int sh = ga.d == 128 ? 4 : 3;  // 16 or 8 lanes per row
+    const int total = gl.k_cap << sh;
+    // four row segments per thread and round, each stage (positions, rows, stores) issued for all four before the
+    // next one: three memory round trips per round instead of twelve
+    constexpr int NB = 4;
+    const size_t head_off = (size_t)b * ga.kv_sb + (size_t)g * ga.kv_sh;
+    const size_t out_off = (size_t)b * gl.o_sb + (size_t)g * gl.o_sh;
+    const int32_t* pos = gl.idx + ((size_t)b * ga.Hkv + g) * gl.k_cap;
+    for (int t0 = tid; t0 < total; t0 += NB * NT) {
+      int src[NB];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int t = t0 + u * NT;
+        src[u] = t < total ? pos[t >> sh] : -1;
+      }
+      uint4 kv[NB], vv[NB];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int seg = (t0 + u * NT) & ((1 << sh) - 1);
+        kv[u] = make_uint4(0, 0, 0, 0);
+        vv[u] = kv[u];
+        if ((uint32_t)src[u] < (uint32_t)ga.N) {  // -1: unused slot; nothing outside [0, N) is dereferenced
+          const size_t off = head_off + (size_t)src[u] * ga.kv_st + seg * 8;
+          kv[u] = *reinterpret_cast<const uint4*>(gl.K + off);
+          vv[u] = *reinterpret_cast<const uint4*>(gl.V + off);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int t = t0 + u * NT;
+        if (t < total) {
+          const size_t o = out_off + (size_t)(t >> sh) * gl.o_st + (t & ((1 << sh) - 1)) * 8;
+          *reinterpret_cast<uint4*>(gl.K_out + o) = kv[u];
+          *reinterpret_cast<uint4*>(gl.V_out + o) = vv[u];
+        }
+      }
+    }
+  };
   if (ly.k_l >= n) {  // keep everything
     for (int j = tid; j < ly.k_cap; j += NT) idx[j] = j < n ? j : -1;
+    gather_unit();
     return;
   }
   const int npre = n - a.alpha;
@@ -678,11 +724,13 @@ __global__ __launch_bounds__(NT) void pool_select_batch_kernel(const SelectBatch
   else
     select_unit<false, kLdsKeys / NT>(raw, a.nrb, rb_stride, a.inv_G, pooled, true, idx, npre, kk, a.alpha, a.pool,
                                       a.pool_w, lkeys, hist, scan32, sel);
+  gather_unit();
 }
 
 }  // namespace
 
-hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipStream_t s) {
+hipError_t launch_pool_select_batch(const SelectBatchArgs& a, const GatherBatchArgs& ga, bool fuse_gather, int nlayers,
+                                    hipStream_t s) {
   static bool attr_set[kMaxDevices];
   const size_t dyn = (size_t)kLdsKeys * sizeof(uint32_t);
   const int dev = current_device_slot();
@@ -693,7 +741,8 @@ hipError_t launch_pool_select_batch(const SelectBatchArgs& a, int nlayers, hipSt
     if (e != hipSuccess) return e;
     attr_set[dev] = true;
   }
-  hipLaunchKernelGGL(pool_select_batch_kernel, dim3(nlayers * a.B * a.Hkv), dim3(NT), dyn, s, a);
+  hipLaunchKernelGGL(pool_select_batch_kernel, dim3(nlayers * a.B * a.Hkv), dim3(NT), dyn, s, a, ga,
+                     fuse_gather ? 1 : 0);
   return hipGetLastError();
 }
 

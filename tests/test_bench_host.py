@@ -39,3 +39,14 @@ def test_tracked_counter_tables_parse():
     f = bench.tracked("pipe_busy.txt", "score_resident:mfma", "llama3-8b-32k", 128, float)
     assert 0.0 < f < 1.0
     assert bench.tracked("traffic_bytes.txt", "score_resident", "no-such-workload", 128, int) is None
+
+
+@pytest.mark.parametrize("name", ["sweep_loop", "xcd_latency", "poll_behind_loads"])
+def test_microbenchmarks_behind_the_profiles_compile_for_gfx950(name, tmp_path):
+    # the stand-alone programs whose recorded outputs sit under profiles/ (cross-compiled here; they run on the GPU machine)
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    src = os.path.join(ROOT, "tests", "microbench", name + ".hip")
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                        "-packed-fp32-ops", src, "-o", str(tmp_path / name)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    assert os.path.exists(os.path.join(ROOT, "profiles", name + "_microbench.md"))
